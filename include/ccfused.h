@@ -1,0 +1,173 @@
+/*
+ * ccfused — fused gradient-reduce + mixed-precision Adam / LAMB step on one GPU's parameter shard
+ * (MI355X, gfx950).  C ABI: plain pointers and sizes, no C++ or framework types.
+ *
+ * The operation is the data-parallel parameter update of the paper (Fig. 4a: all-reduce of the
+ * gradients with "+", then the Adam moments, bias corrections and parameter update) after the
+ * schedule of Fig. 4b has been applied: the all-reduce is split into reduce-scatter + all-gather,
+ * the all-gather is moved behind the update, m and v live only on the owning rank, and the
+ * reduce, the update and the emission of the new fp16 parameters are fused into one kernel
+ * (Section 3.3 "AllReduce Fuse", Section 5.2).  This library is the compute side of that fused
+ * kernel on ONE rank: the R incoming fp16 gradient slices are R device buffers, the reduced value
+ * never goes through memory, and the new parameters are written once as fp32 master weights and
+ * once as the fp16 values that would be all-gathered.  Tensors are scattered (one buffer per
+ * layer) and indexed through a chunk table built once on the host (Section 5.4).
+ *
+ * Conventions
+ *   - "device" pointers are HIP device memory on the current device, owned by the caller.
+ *   - fp16 data is passed as uint16_t bit patterns (IEEE binary16).
+ *   - Every call returns CC_OK (0) or a negative cc_status; nothing throws.  cc_last_error() gives a
+ *     thread-local message for the last failing call on this thread.
+ *   - Step calls are asynchronous: they enqueue kernels on `hip_stream` (a hipStream_t passed as
+ *     void*, NULL = the default stream) and never synchronise.  Arguments are validated on the host
+ *     before anything is enqueued; a rejected call enqueues nothing.
+ *   - A plan may be used by one stream at a time: its scratch buffers are shared by all of its calls.
+ */
+#ifndef CCFUSED_H
+#define CCFUSED_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CC_MAX_R 16            /* most gradient slices one element can be reduced from */
+#define CC_VERSION 100
+
+typedef enum cc_status {
+    CC_OK = 0,
+    CC_ERR_NULL = -1,          /* a required pointer is NULL */
+    CC_ERR_ARG = -2,           /* a count, size or hyper-parameter is out of range */
+    CC_ERR_ALIGN = -3,         /* a tensor base pointer is not 16-byte aligned */
+    CC_ERR_ALIAS = -4,         /* in/out buffers alias in a mode that forbids it */
+    CC_ERR_HIP = -5,           /* a HIP runtime call failed (no device, out of memory, launch error) */
+    CC_ERR_NOMEM = -6          /* host allocation failed */
+} cc_status;
+
+/*
+ * One tensor of the shard (the p, g, m, v of Fig. 4, restricted to this rank's slice).
+ * All pointers are device pointers to `numel` elements and must be 16-byte aligned (numel == 0:
+ * pointers are ignored).  w/m/v outputs may be the same buffers as the inputs (in place) or
+ * different ones (out of place, so that a skipped step leaves the inputs untouched); partial
+ * overlap is an error.  Only grad[0..R-1] are read.
+ */
+typedef struct cc_tensor {
+    uint64_t        numel;
+    const float    *w_in;              /* fp32 master weights before the step */
+    const float    *m_in;              /* first moment  */
+    const float    *v_in;              /* second moment */
+    float          *w_out;             /* fp32 master weights after the step */
+    float          *m_out;
+    float          *v_out;
+    uint16_t       *w16_out;           /* fp16 copy of w_out, round to nearest even (what is all-gathered) */
+    const uint16_t *grad[CC_MAX_R];    /* R fp16 gradient slices, one per contributing rank */
+    float           weight_decay;      /* per tensor (0 for bias / LayerNorm) */
+} cc_tensor;
+
+/*
+ * Scalars of one step (lr, beta1, beta2, t of Fig. 4a; epsilon, decay, loss scale as in standard
+ * mixed-precision training).  The fp32 values given here are the definition: bias corrections
+ * 1 - beta^step are formed from them in double on the host.
+ */
+typedef struct cc_hparams {
+    float   lr;
+    float   beta1;             /* in [0, 1) */
+    float   beta2;             /* in [0, 1) */
+    float   eps;               /* >= 0; added to the root of the bias-corrected second moment */
+    float   loss_scale;        /* > 0, finite; the reduced gradient is divided by it once */
+    int32_t step;              /* t, 1-based */
+    int32_t grad_average;      /* 0: sum of the R slices; 1: also divide by R */
+    int32_t adam_mode;         /* 1: decoupled weight decay (u += wd*w); 0: L2 (g += wd*w). LAMB: 1 only */
+    int32_t skip_mode;         /* 0: whole-step skip on overflow, needs out buffers distinct from in
+                                     buffers; the caller adopts the out buffers only if the flag is 0.
+                                  1: per-element guard: an element whose reduced gradient is inf/NaN
+                                     keeps its w, m, v; allowed in place.  LAMB: 0 only */
+} cc_hparams;
+
+typedef struct cc_plan cc_plan;   /* opaque: device copy of the tensor list, chunk table, scratch */
+
+/* ---- host-only helpers of the chunk table (Section 5.4); no device is touched ---- */
+
+/* Number of chunks a tensor list needs: sum over tensors of ceil(numel / chunk_elems).
+ * chunk_elems must be a positive multiple of 1024 (0 selects the default). Returns < 0 on error. */
+int64_t cc_chunk_count(const uint64_t *numels, int32_t T, int32_t chunk_elems);
+
+/* Fills `table` (host memory, capacity entries of 2 x uint32: tensor index, chunk index inside the
+ * tensor) in tensor order.  Returns the number of entries written, or < 0 on error / too small. */
+int64_t cc_chunk_table_fill(const uint64_t *numels, int32_t T, int32_t chunk_elems,
+                            uint32_t *table, int64_t capacity);
+
+/* Default chunk size in elements (a tuning choice of this library; the paper's buckets hold 2^10). */
+int32_t cc_default_chunk_elems(void);
+
+/* ---- plan ---- */
+
+/*
+ * Validates the T tensors (host array, copied) and builds the device-side descriptor array and chunk
+ * table once, like the paper's wrapper pre-computes bucket pointers (Section 5.5).  R = number of
+ * gradient slices per tensor, 1..CC_MAX_R.  chunk_elems: 0 = default, else a positive multiple of 1024.
+ * The plan owns only its own tables and scratch; it keeps raw copies of the caller's pointers, which
+ * must stay valid while the plan is used.  Tensors with numel == 0 are legal and produce no chunks.
+ */
+int cc_plan_create(const cc_tensor *tensors, int32_t T, int32_t R, int32_t chunk_elems, cc_plan **out);
+int cc_plan_destroy(cc_plan *plan);
+
+/* Totals of a plan: elements, chunks and bytes of table memory on the device. */
+int cc_plan_info(const cc_plan *plan, uint64_t *numel, int64_t *chunks, uint64_t *table_bytes);
+
+/* ---- fused steps (one pass over HBM per sweep) ---- */
+
+/*
+ * Adam (Fig. 4a with the schedule of Fig. 4b).  Per element i of every tensor, in fp32:
+ *   S = g_0[i] + g_1[i] + ... + g_{R-1}[i]   (fixed rank order)     gh = S / (loss_scale * (avg ? R : 1))
+ *   m' = beta1 m + (1-beta1) gh      v' = beta2 v + (1-beta2) gh^2
+ *   u  = (m'/(1-beta1^t)) / (sqrt(v'/(1-beta2^t)) + eps) + wd w     w' = w - lr u     w16 = fp16(w')
+ * *d_overflow_flag (device int32) is cleared by the call and set to 1 if any S is inf or NaN.
+ * skip_mode 0: outputs are written unconditionally to the (distinct) out buffers; they are valid only
+ * if the flag reads 0 afterwards.  skip_mode 1: see cc_hparams.
+ */
+int cc_fused_adam_step(cc_plan *plan, const cc_hparams *hp, int32_t *d_overflow_flag, void *hip_stream);
+
+/*
+ * LAMB, two sweeps around a per-tensor reduction (Section 5.2 "Tensor Reduction": each rank reduces
+ * locally).  Phase 1 reduces the gradients, writes m', v' and accumulates sum(w^2), sum(u^2) per tensor
+ * (u as above, w before the update).  Phase 2 forms ratio = ||w||/||u|| (1 if either norm is 0) and
+ * writes w' = w - lr ratio u and w16.  On overflow phase 2 leaves w_out and w16_out untouched.
+ * cc_fused_lamb_step = phase 1 then phase 2.  The two phases are exported separately so that a
+ * cross-rank sum of the per-tensor norms can be placed between them.
+ */
+int cc_fused_lamb_step(cc_plan *plan, const cc_hparams *hp, int32_t *d_overflow_flag, void *hip_stream);
+int cc_fused_lamb_phase1(cc_plan *plan, const cc_hparams *hp, int32_t *d_overflow_flag, void *hip_stream);
+int cc_fused_lamb_phase2(cc_plan *plan, const cc_hparams *hp, const int32_t *d_overflow_flag, void *hip_stream);
+
+/* Device pointer to the plan's T x 2 doubles {sum w^2, sum u^2}, valid after phase 1 has run. */
+int cc_lamb_norm_buffer(cc_plan *plan, double **d_sums);
+
+/* Waits for `hip_stream`, then copies those T x 2 doubles to host memory `h_sums` (synchronous). */
+int cc_lamb_norms_read(cc_plan *plan, double *h_sums, void *hip_stream);
+
+/* ---- unfused reference pipelines (the AR-Opt shape of Section 6.1.1: reduce, then optimizer, then cast) ---- */
+
+/*
+ * Same results as the fused calls, computed by separate kernels with the reduced gradient stored to and
+ * re-read from an fp32 buffer owned by the plan (allocated on first use): reduce R slices -> fp32,
+ * optimizer kernel(s) on the reduced gradient, fp32 -> fp16 cast.  The flag is known after the reduce
+ * kernel, so in skip_mode 0 the later kernels leave every output untouched on overflow.
+ */
+int cc_unfused_adam_step(cc_plan *plan, const cc_hparams *hp, int32_t *d_overflow_flag, void *hip_stream);
+int cc_unfused_lamb_step(cc_plan *plan, const cc_hparams *hp, int32_t *d_overflow_flag, void *hip_stream);
+
+/* ---- measurement aid ---- */
+
+/* Plain streaming copy of `bytes` (multiple of 16, both pointers 16-byte aligned) device to device with
+ * the same launch shape as the fused kernels; gives the practical HBM ceiling and calibrates counters. */
+int cc_copy_probe(void *d_dst, const void *d_src, uint64_t bytes, void *hip_stream);
+
+const char *cc_last_error(void);
+int cc_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CCFUSED_H */

@@ -1,0 +1,464 @@
+// Host side of ccfused: argument checks, the chunk table (Section 5.4), step scalars, kernel launches.
+// Everything that touches a parameter runs in the kernels of kernels.hip.h; nothing here computes an update.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "ccfused.h"
+#include "kernels.hip.h"
+
+using namespace ccf;
+
+namespace {
+
+constexpr int32_t kDefaultChunkElems = 4096;
+
+thread_local char g_err[512] = "";
+
+int fail(cc_status code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return (int)code;
+}
+
+#define HIP_TRY(expr)                                                                              \
+    do {                                                                                           \
+        hipError_t e_ = (expr);                                                                    \
+        if (e_ != hipSuccess) return fail(CC_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_));     \
+    } while (0)
+
+int32_t resolve_chunk(int32_t chunk_elems)
+{
+    if (chunk_elems == 0) return kDefaultChunkElems;
+    if (chunk_elems < 0 || chunk_elems % 1024 != 0) return -1;
+    return chunk_elems;
+}
+
+bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+// 0: disjoint, 1: identical, -1: partial overlap
+int overlap(const void *a, const void *b, uint64_t bytes)
+{
+    const uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b);
+    if (x == y) return 1;
+    if (x + bytes <= y || y + bytes <= x) return 0;
+    return -1;
+}
+
+}  // namespace
+
+struct cc_plan {
+    int32_t T = 0, R = 0, chunk_elems = 0;
+    int64_t chunks = 0;
+    uint64_t numel = 0;
+    bool in_place = false;                  // some tensor has out == in
+    std::vector<DevTensor> host_tensors;    // host mirror of the device descriptors
+    std::vector<uint64_t> gsum_offset;      // element offset of each tensor in the unfused fp32 buffer
+    uint64_t gsum_elems = 0;
+    DevTensor *d_tensors = nullptr;
+    Chunk *d_chunks = nullptr;
+    double *d_partials = nullptr;           // 2 per chunk (LAMB)
+    double *d_sums = nullptr;               // 2 per tensor (LAMB)
+    float *d_gsum = nullptr;                // unfused pipelines, allocated on first use
+};
+
+extern "C" {
+
+const char *cc_last_error(void) { return g_err; }
+int cc_version(void) { return CC_VERSION; }
+int32_t cc_default_chunk_elems(void) { return kDefaultChunkElems; }
+
+int64_t cc_chunk_count(const uint64_t *numels, int32_t T, int32_t chunk_elems)
+{
+    if (!numels && T > 0) return fail(CC_ERR_NULL, "cc_chunk_count: numels is NULL");
+    if (T < 0) return fail(CC_ERR_ARG, "cc_chunk_count: T = %d", T);
+    const int32_t ce = resolve_chunk(chunk_elems);
+    if (ce < 0) return fail(CC_ERR_ARG, "chunk_elems = %d is not a positive multiple of 1024", chunk_elems);
+    int64_t total = 0;
+    for (int32_t t = 0; t < T; ++t) {
+        const uint64_t c = (numels[t] + (uint64_t)ce - 1) / (uint64_t)ce;
+        if (c > 0xffffffffull) return fail(CC_ERR_ARG, "tensor %d has too many chunks", t);
+        total += (int64_t)c;
+    }
+    if (total > 0x7fffffffll) return fail(CC_ERR_ARG, "%lld chunks exceed one launch; use a larger chunk_elems", (long long)total);
+    return total;
+}
+
+int64_t cc_chunk_table_fill(const uint64_t *numels, int32_t T, int32_t chunk_elems, uint32_t *table, int64_t capacity)
+{
+    const int64_t need = cc_chunk_count(numels, T, chunk_elems);
+    if (need < 0) return need;
+    if (!table && need > 0) return fail(CC_ERR_NULL, "cc_chunk_table_fill: table is NULL");
+    if (capacity < need) return fail(CC_ERR_ARG, "table capacity %lld < %lld chunks", (long long)capacity, (long long)need);
+    const uint64_t ce = (uint64_t)resolve_chunk(chunk_elems);
+    int64_t k = 0;
+    for (int32_t t = 0; t < T; ++t) {
+        const uint64_t c = (numels[t] + ce - 1) / ce;
+        for (uint64_t i = 0; i < c; ++i, ++k) {
+            table[2 * k] = (uint32_t)t;
+            table[2 * k + 1] = (uint32_t)i;
+        }
+    }
+    return k;
+}
+
+int cc_plan_create(const cc_tensor *tensors, int32_t T, int32_t R, int32_t chunk_elems, cc_plan **out)
+{
+    if (!out) return fail(CC_ERR_NULL, "cc_plan_create: out is NULL");
+    *out = nullptr;
+    if (!tensors) return fail(CC_ERR_NULL, "cc_plan_create: tensors is NULL");
+    if (T <= 0) return fail(CC_ERR_ARG, "cc_plan_create: T = %d must be positive", T);
+    if (R < 1 || R > CC_MAX_R) return fail(CC_ERR_ARG, "cc_plan_create: R = %d outside 1..%d", R, CC_MAX_R);
+    const int32_t ce = resolve_chunk(chunk_elems);
+    if (ce < 0) return fail(CC_ERR_ARG, "chunk_elems = %d is not a positive multiple of 1024", chunk_elems);
+
+    bool in_place = false;
+    std::vector<uint64_t> numels((size_t)T);
+    for (int32_t t = 0; t < T; ++t) {
+        const cc_tensor &x = tensors[t];
+        numels[(size_t)t] = x.numel;
+        if (x.numel == 0) continue;
+        if (!std::isfinite(x.weight_decay)) return fail(CC_ERR_ARG, "tensor %d: weight_decay is not finite", t);
+        const void *ptrs[7] = {x.w_in, x.m_in, x.v_in, x.w_out, x.m_out, x.v_out, x.w16_out};
+        static const char *names[7] = {"w_in", "m_in", "v_in", "w_out", "m_out", "v_out", "w16_out"};
+        for (int k = 0; k < 7; ++k) {
+            if (!ptrs[k]) return fail(CC_ERR_NULL, "tensor %d: %s is NULL", t, names[k]);
+            if (misaligned(ptrs[k])) return fail(CC_ERR_ALIGN, "tensor %d: %s is not 16-byte aligned", t, names[k]);
+        }
+        for (int r = 0; r < R; ++r) {
+            if (!x.grad[r]) return fail(CC_ERR_NULL, "tensor %d: grad[%d] is NULL", t, r);
+            if (misaligned(x.grad[r])) return fail(CC_ERR_ALIGN, "tensor %d: grad[%d] is not 16-byte aligned", t, r);
+        }
+        const uint64_t bytes = x.numel * 4;
+        const int ow = overlap(x.w_in, x.w_out, bytes), om = overlap(x.m_in, x.m_out, bytes), ov = overlap(x.v_in, x.v_out, bytes);
+        if (ow < 0 || om < 0 || ov < 0) return fail(CC_ERR_ALIAS, "tensor %d: in and out buffers overlap partially", t);
+        in_place = in_place || ow || om || ov;
+    }
+    const int64_t chunks = cc_chunk_count(numels.data(), T, ce);
+    if (chunks < 0) return (int)chunks;
+
+    cc_plan *p = new (std::nothrow) cc_plan;
+    if (!p) return fail(CC_ERR_NOMEM, "cc_plan_create: out of host memory");
+    p->T = T; p->R = R; p->chunk_elems = ce; p->chunks = chunks; p->in_place = in_place;
+    std::vector<uint32_t> table;
+    try {
+        p->host_tensors.resize((size_t)T);
+        p->gsum_offset.resize((size_t)T);
+        table.resize((size_t)(2 * chunks) + 2);
+    } catch (const std::bad_alloc &) {
+        delete p;
+        return fail(CC_ERR_NOMEM, "cc_plan_create: out of host memory");
+    }
+    uint64_t first = 0, goff = 0, total = 0;
+    for (int32_t t = 0; t < T; ++t) {
+        const cc_tensor &x = tensors[t];
+        DevTensor &d = p->host_tensors[(size_t)t];
+        std::memset(&d, 0, sizeof(d));
+        d.numel = x.numel;
+        d.w_in = x.w_in; d.m_in = x.m_in; d.v_in = x.v_in;
+        d.w_out = x.w_out; d.m_out = x.m_out; d.v_out = x.v_out;
+        d.w16 = x.w16_out;
+        for (int r = 0; r < R; ++r) d.grad[r] = x.grad[r];
+        d.wd = x.weight_decay;
+        d.first_chunk = (uint32_t)first;
+        d.num_chunks = (uint32_t)((x.numel + (uint64_t)ce - 1) / (uint64_t)ce);
+        first += d.num_chunks;
+        p->gsum_offset[(size_t)t] = goff;
+        goff += (x.numel + 7) / 8 * 8;            // every tensor starts 32-byte aligned in the fp32 buffer
+        total += x.numel;
+    }
+    p->numel = total;
+    p->gsum_elems = goff;
+    cc_chunk_table_fill(numels.data(), T, ce, table.data(), chunks);
+
+#define PLAN_TRY(expr)                                                                             \
+    do {                                                                                           \
+        hipError_t e_ = (expr);                                                                    \
+        if (e_ != hipSuccess) {                                                                    \
+            fail(CC_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_));                              \
+            cc_plan_destroy(p);                                                                    \
+            return CC_ERR_HIP;                                                                     \
+        }                                                                                          \
+    } while (0)
+    PLAN_TRY(hipMalloc((void **)&p->d_tensors, sizeof(DevTensor) * (size_t)T));
+    PLAN_TRY(hipMemcpy(p->d_tensors, p->host_tensors.data(), sizeof(DevTensor) * (size_t)T, hipMemcpyHostToDevice));
+    PLAN_TRY(hipMalloc((void **)&p->d_chunks, sizeof(Chunk) * (size_t)(chunks + 1)));
+    if (chunks > 0) PLAN_TRY(hipMemcpy(p->d_chunks, table.data(), sizeof(Chunk) * (size_t)chunks, hipMemcpyHostToDevice));
+    PLAN_TRY(hipMalloc((void **)&p->d_partials, sizeof(double) * 2 * (size_t)(chunks + 1)));
+    PLAN_TRY(hipMalloc((void **)&p->d_sums, sizeof(double) * 2 * (size_t)T));
+    PLAN_TRY(hipMemset(p->d_sums, 0, sizeof(double) * 2 * (size_t)T));
+#undef PLAN_TRY
+    *out = p;
+    return CC_OK;
+}
+
+int cc_plan_destroy(cc_plan *p)
+{
+    if (!p) return CC_OK;
+    if (p->d_tensors) (void)hipFree(p->d_tensors);
+    if (p->d_chunks) (void)hipFree(p->d_chunks);
+    if (p->d_partials) (void)hipFree(p->d_partials);
+    if (p->d_sums) (void)hipFree(p->d_sums);
+    if (p->d_gsum) (void)hipFree(p->d_gsum);
+    delete p;
+    return CC_OK;
+}
+
+int cc_plan_info(const cc_plan *p, uint64_t *numel, int64_t *chunks, uint64_t *table_bytes)
+{
+    if (!p) return fail(CC_ERR_NULL, "cc_plan_info: plan is NULL");
+    if (numel) *numel = p->numel;
+    if (chunks) *chunks = p->chunks;
+    if (table_bytes) *table_bytes = sizeof(Chunk) * (uint64_t)p->chunks + sizeof(DevTensor) * (uint64_t)p->T;
+    return CC_OK;
+}
+
+int cc_lamb_norm_buffer(cc_plan *p, double **d_sums)
+{
+    if (!p || !d_sums) return fail(CC_ERR_NULL, "cc_lamb_norm_buffer: NULL argument");
+    *d_sums = p->d_sums;
+    return CC_OK;
+}
+
+int cc_lamb_norms_read(cc_plan *p, double *h_sums, void *stream)
+{
+    if (!p || !h_sums) return fail(CC_ERR_NULL, "cc_lamb_norms_read: NULL argument");
+    HIP_TRY(hipStreamSynchronize((hipStream_t)stream));
+    HIP_TRY(hipMemcpy(h_sums, p->d_sums, sizeof(double) * 2 * (size_t)p->T, hipMemcpyDeviceToHost));
+    return CC_OK;
+}
+
+}  // extern "C"
+
+namespace {
+
+enum class Opt { Adam, Lamb };
+
+int check_step(const cc_plan *p, const cc_hparams *hp, const void *flag, Opt opt, StepScalars *s)
+{
+    if (!p) return fail(CC_ERR_NULL, "plan is NULL");
+    if (!hp) return fail(CC_ERR_NULL, "hparams is NULL");
+    if (!flag) return fail(CC_ERR_NULL, "d_overflow_flag is NULL");
+    if (hp->step < 1) return fail(CC_ERR_ARG, "step = %d must be >= 1", hp->step);
+    if (!(hp->beta1 >= 0.f && hp->beta1 < 1.f)) return fail(CC_ERR_ARG, "beta1 = %g outside [0, 1)", (double)hp->beta1);
+    if (!(hp->beta2 >= 0.f && hp->beta2 < 1.f)) return fail(CC_ERR_ARG, "beta2 = %g outside [0, 1)", (double)hp->beta2);
+    if (!(hp->loss_scale > 0.f) || !std::isfinite(hp->loss_scale)) return fail(CC_ERR_ARG, "loss_scale = %g must be positive and finite", (double)hp->loss_scale);
+    if (!std::isfinite(hp->lr)) return fail(CC_ERR_ARG, "lr is not finite");
+    if (!(hp->eps >= 0.f) || !std::isfinite(hp->eps)) return fail(CC_ERR_ARG, "eps = %g must be >= 0 and finite", (double)hp->eps);
+    if (hp->grad_average != 0 && hp->grad_average != 1) return fail(CC_ERR_ARG, "grad_average = %d", hp->grad_average);
+    if (hp->adam_mode != 0 && hp->adam_mode != 1) return fail(CC_ERR_ARG, "adam_mode = %d", hp->adam_mode);
+    if (hp->skip_mode != 0 && hp->skip_mode != 1) return fail(CC_ERR_ARG, "skip_mode = %d", hp->skip_mode);
+    if (opt == Opt::Lamb && (hp->adam_mode != 1 || hp->skip_mode != 0))
+        return fail(CC_ERR_ARG, "LAMB supports adam_mode = 1 and skip_mode = 0 only");
+    if (hp->skip_mode == 0 && p->in_place)
+        return fail(CC_ERR_ALIAS, "skip_mode 0 (whole-step skip) needs out buffers distinct from the in buffers");
+    const double b1 = hp->beta1, b2 = hp->beta2;
+    const double c1 = 1.0 - std::pow(b1, (double)hp->step), c2 = 1.0 - std::pow(b2, (double)hp->step);
+    s->beta1 = hp->beta1;
+    s->beta2 = hp->beta2;
+    s->omb1 = (float)(1.0 - b1);
+    s->omb2 = (float)(1.0 - b2);
+    s->rc1 = (float)(1.0 / c1);
+    s->rc2 = (float)(1.0 / c2);
+    s->eps = hp->eps;
+    s->lr = hp->lr;
+    s->inv_div = (float)(1.0 / ((double)hp->loss_scale * (hp->grad_average ? (double)p->R : 1.0)));
+    s->chunk_elems = (uint32_t)p->chunk_elems;
+    return CC_OK;
+}
+
+int launched(const char *what)
+{
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(CC_ERR_HIP, "launch of %s failed: %s", what, hipGetErrorString(e));
+    return CC_OK;
+}
+
+// Allocates the fp32 reduced-gradient buffer of the unfused pipelines and points every descriptor at it.
+int ensure_gsum(cc_plan *p)
+{
+    if (p->d_gsum) return CC_OK;
+    HIP_TRY(hipMalloc((void **)&p->d_gsum, sizeof(float) * (size_t)(p->gsum_elems + 8)));
+    for (int32_t t = 0; t < p->T; ++t) p->host_tensors[(size_t)t].gsum = p->d_gsum + p->gsum_offset[(size_t)t];
+    HIP_TRY(hipMemcpy(p->d_tensors, p->host_tensors.data(), sizeof(DevTensor) * (size_t)p->T, hipMemcpyHostToDevice));
+    return CC_OK;
+}
+
+#define FOR_EACH_R(X) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13) X(14) X(15) X(16)
+
+template <int MODE>
+void launch_fused_adam(const cc_plan *p, const StepScalars &s, int32_t *flag, hipStream_t st)
+{
+    const dim3 grid((unsigned)p->chunks), block(kBlock);
+    switch (p->R) {
+#define CASE(r) case r: hipLaunchKernelGGL((fused_adam_kernel<r, MODE>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag); break;
+        FOR_EACH_R(CASE)
+#undef CASE
+    }
+}
+
+void launch_lamb_phase1(const cc_plan *p, const StepScalars &s, int32_t *flag, hipStream_t st)
+{
+    const dim3 grid((unsigned)p->chunks), block(kBlock);
+    switch (p->R) {
+#define CASE(r) case r: hipLaunchKernelGGL((lamb_phase1_kernel<r, false>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, p->d_partials, flag); break;
+        FOR_EACH_R(CASE)
+#undef CASE
+    }
+}
+
+void launch_reduce(const cc_plan *p, const StepScalars &s, int32_t *flag, hipStream_t st)
+{
+    const dim3 grid((unsigned)p->chunks), block(kBlock);
+    switch (p->R) {
+#define CASE(r) case r: hipLaunchKernelGGL((reduce_kernel<r>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag); break;
+        FOR_EACH_R(CASE)
+#undef CASE
+    }
+}
+
+int clear_flag(int32_t *flag, hipStream_t st)
+{
+    // a one-thread kernel rather than a memset node, so that the call can be captured into a HIP graph
+    hipLaunchKernelGGL(clear_flag_kernel, dim3(1), dim3(1), 0, st, flag);
+    return launched("clear_flag_kernel");
+}
+
+int lamb_phase2_impl(cc_plan *p, const StepScalars &s, const int32_t *flag, hipStream_t st, bool emit16)
+{
+    if (p->chunks == 0) return CC_OK;
+    const dim3 grid((unsigned)p->chunks), block(kBlock);
+    if (emit16) hipLaunchKernelGGL((lamb_phase2_kernel<true>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, p->d_sums, flag);
+    else hipLaunchKernelGGL((lamb_phase2_kernel<false>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, p->d_sums, flag);
+    return launched("lamb_phase2_kernel");
+}
+
+int lamb_norms(cc_plan *p, hipStream_t st)
+{
+    hipLaunchKernelGGL(lamb_norms_kernel, dim3((unsigned)p->T), dim3(kBlock), 0, st, p->d_tensors, p->d_partials, p->d_sums);
+    return launched("lamb_norms_kernel");
+}
+
+}  // namespace
+
+extern "C" {
+
+int cc_fused_adam_step(cc_plan *p, const cc_hparams *hp, int32_t *flag, void *stream)
+{
+    StepScalars s;
+    int rc = check_step(p, hp, flag, Opt::Adam, &s);
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    if ((rc = clear_flag(flag, st))) return rc;
+    if (p->chunks == 0) return CC_OK;
+    const int mode = (hp->skip_mode == 1 ? kModeGuard : 0) | (hp->adam_mode == 0 ? kModeL2 : 0);
+    switch (mode) {
+        case 0: launch_fused_adam<0>(p, s, flag, st); break;
+        case 1: launch_fused_adam<1>(p, s, flag, st); break;
+        case 2: launch_fused_adam<2>(p, s, flag, st); break;
+        default: launch_fused_adam<3>(p, s, flag, st); break;
+    }
+    return launched("fused_adam_kernel");
+}
+
+int cc_fused_lamb_phase1(cc_plan *p, const cc_hparams *hp, int32_t *flag, void *stream)
+{
+    StepScalars s;
+    int rc = check_step(p, hp, flag, Opt::Lamb, &s);
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    if ((rc = clear_flag(flag, st))) return rc;
+    if (p->chunks > 0) {
+        launch_lamb_phase1(p, s, flag, st);
+        if ((rc = launched("lamb_phase1_kernel"))) return rc;
+    }
+    return lamb_norms(p, st);
+}
+
+int cc_fused_lamb_phase2(cc_plan *p, const cc_hparams *hp, const int32_t *flag, void *stream)
+{
+    StepScalars s;
+    int rc = check_step(p, hp, flag, Opt::Lamb, &s);
+    if (rc) return rc;
+    return lamb_phase2_impl(p, s, flag, (hipStream_t)stream, true);
+}
+
+int cc_fused_lamb_step(cc_plan *p, const cc_hparams *hp, int32_t *flag, void *stream)
+{
+    const int rc = cc_fused_lamb_phase1(p, hp, flag, stream);
+    if (rc) return rc;
+    return cc_fused_lamb_phase2(p, hp, flag, stream);
+}
+
+int cc_unfused_adam_step(cc_plan *p, const cc_hparams *hp, int32_t *flag, void *stream)
+{
+    StepScalars s;
+    int rc = check_step(p, hp, flag, Opt::Adam, &s);
+    if (rc) return rc;
+    if ((rc = ensure_gsum(p))) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    if ((rc = clear_flag(flag, st))) return rc;
+    if (p->chunks == 0) return CC_OK;
+    const dim3 grid((unsigned)p->chunks), block(kBlock);
+    launch_reduce(p, s, flag, st);
+    if ((rc = launched("reduce_kernel"))) return rc;
+    const int mode = (hp->skip_mode == 1 ? kModeGuard : 0) | (hp->adam_mode == 0 ? kModeL2 : 0);
+    switch (mode) {
+        case 0: hipLaunchKernelGGL((adam_from_sum_kernel<0>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag); break;
+        case 1: hipLaunchKernelGGL((adam_from_sum_kernel<1>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag); break;
+        case 2: hipLaunchKernelGGL((adam_from_sum_kernel<2>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag); break;
+        default: hipLaunchKernelGGL((adam_from_sum_kernel<3>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag); break;
+    }
+    if ((rc = launched("adam_from_sum_kernel"))) return rc;
+    hipLaunchKernelGGL(cast_kernel, grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag, hp->skip_mode == 0 ? 1 : 0);
+    return launched("cast_kernel");
+}
+
+int cc_unfused_lamb_step(cc_plan *p, const cc_hparams *hp, int32_t *flag, void *stream)
+{
+    StepScalars s;
+    int rc = check_step(p, hp, flag, Opt::Lamb, &s);
+    if (rc) return rc;
+    if ((rc = ensure_gsum(p))) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    if ((rc = clear_flag(flag, st))) return rc;
+    if (p->chunks > 0) {
+        const dim3 grid((unsigned)p->chunks), block(kBlock);
+        launch_reduce(p, s, flag, st);
+        if ((rc = launched("reduce_kernel"))) return rc;
+        hipLaunchKernelGGL((lamb_phase1_kernel<1, true>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, p->d_partials, flag);
+        if ((rc = launched("lamb_phase1_kernel"))) return rc;
+    }
+    if ((rc = lamb_norms(p, st))) return rc;
+    if ((rc = lamb_phase2_impl(p, s, flag, st, false))) return rc;
+    if (p->chunks > 0) {
+        const dim3 grid((unsigned)p->chunks), block(kBlock);
+        hipLaunchKernelGGL(cast_kernel, grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag, 1);
+        return launched("cast_kernel");
+    }
+    return CC_OK;
+}
+
+int cc_copy_probe(void *dst, const void *src, uint64_t bytes, void *stream)
+{
+    if (!dst || !src) return fail(CC_ERR_NULL, "cc_copy_probe: NULL pointer");
+    if (bytes % 16 != 0) return fail(CC_ERR_ARG, "cc_copy_probe: bytes = %llu is not a multiple of 16", (unsigned long long)bytes);
+    if (misaligned(dst) || misaligned(src)) return fail(CC_ERR_ALIGN, "cc_copy_probe: pointers must be 16-byte aligned");
+    if (bytes == 0) return CC_OK;
+    const uint64_t n16 = bytes / 16;
+    const uint64_t per_block = (uint64_t)kBlock * 4;
+    const uint64_t blocks = (n16 + per_block - 1) / per_block;
+    if (blocks > 0x7fffffffull) return fail(CC_ERR_ARG, "cc_copy_probe: too large for one launch");
+    hipLaunchKernelGGL(copy_kernel, dim3((unsigned)blocks), dim3(kBlock), 0, (hipStream_t)stream, (u32x4 *)dst, (const u32x4 *)src, n16);
+    return launched("copy_kernel");
+}
+
+}  // extern "C"

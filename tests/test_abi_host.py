@@ -1,0 +1,151 @@
+"""Host-side checks that need no GPU: the library loads and exports what the header declares, the chunk table
+is right, bad arguments are rejected before any device call, and the workload lists have the published sizes."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2105_05720_amd import binding as cc
+from paper_2105_05720_amd import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "ccfused.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(cc_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = cc.load()
+    names = declared_functions()
+    assert len(names) >= 17
+    for n in names:
+        assert hasattr(lib, n), "libccfused.so does not export %s" % n
+        assert n in cc.EXPORTS, "binding does not type %s" % n
+        assert hasattr(cc, n), "binding has no function %s" % n
+    assert set(cc.EXPORTS) == set(names)
+    assert cc.cc_version() == 100
+
+
+def test_struct_layout_matches_header():
+    assert C.sizeof(cc.cc_tensor) == 8 + 7 * 8 + 16 * 8 + 8      # numel, 7 pointers, 16 gradient pointers, float + pad
+    assert cc.cc_tensor.weight_decay.offset == 192
+    assert C.sizeof(cc.cc_hparams) == 36
+
+
+def brute_table(numels, ce):
+    out = []
+    for t, n in enumerate(numels):
+        for i in range(-(-n // ce)):
+            out.append((t, i))
+    return out
+
+
+@pytest.mark.parametrize("ce", [1024, 4096, 8192])
+def test_chunk_table_against_brute_force(ce):
+    rng = np.random.default_rng(ce)
+    numels = [0, 1, ce - 1, ce, ce + 1, 5 * ce, 0, 3] + [int(x) for x in rng.integers(0, 20 * ce, 20)]
+    assert cc.cc_chunk_count(numels, ce) == len(brute_table(numels, ce))
+    assert cc.cc_chunk_table_fill(numels, ce) == brute_table(numels, ce)
+    # every element is covered exactly once and every chunk start is a multiple of 8 elements (16-byte accesses)
+    covered = {t: 0 for t in range(len(numels))}
+    for t, i in cc.cc_chunk_table_fill(numels, ce):
+        assert (i * ce) % 8 == 0 and i * ce < numels[t]
+        covered[t] += min(ce, numels[t] - i * ce)
+    assert all(covered[t] == n for t, n in enumerate(numels))
+
+
+def test_chunk_table_default_and_errors():
+    assert cc.cc_default_chunk_elems() % 1024 == 0
+    assert cc.cc_chunk_count([10000], 0) == -(-10000 // cc.cc_default_chunk_elems())
+    assert cc.cc_chunk_count([], 1024) == 0
+    for bad in (1000, -1024, 1):
+        with pytest.raises(cc.CcError) as e:
+            cc.cc_chunk_count([10], bad)
+        assert e.value.code == cc.CC_ERR_ARG
+    with pytest.raises(cc.CcError) as e:
+        cc.cc_chunk_table_fill([5000, 5000], 1024, capacity=3)
+    assert e.value.code == cc.CC_ERR_ARG and "capacity" in str(e.value)
+    with pytest.raises(cc.CcError):
+        cc.cc_chunk_count([2 ** 45], 1024)                      # would not fit one launch
+
+
+def test_paper_bucket_table_accounting():
+    """Section 5.4: 12 bytes per 2^10 elements; 0.6 % of a 334 M-element fp16 model."""
+    enc_emb = sum(s.numel for s in W.bert_large_list() if not s.name.startswith(("pooler", "mlm", "nsp")))
+    assert enc_emb == 334_092_288
+    assert W.table_bytes_paper(enc_emb) == 12 * 326_262
+    assert round(100 * W.table_bytes_paper(enc_emb) / (2 * enc_emb), 1) == 0.6
+    assert W.table_bytes_paper(1) == 12 and W.table_bytes_paper(1025) == 24
+
+
+def test_workload_sizes():
+    want = {1: (1, 1_048_576), 2: (398, 336_226_108), 3: (398, 336_226_108), 4: (580, 1_557_611_200), 5: (73, 1_039_629_312)}
+    for i, (T, N) in want.items():
+        c = W.config(i)
+        assert (len(c.params), c.numel) == (T, N)
+    c4 = W.config(4)
+    names = [s.name for s in c4.params]
+    k = names.index(W.CFG4_INF_TENSOR)
+    assert c4.params[k].numel == 1600 * 6400 and W.CFG4_INF_INDEX < c4.params[k].numel
+    keys = {W.seed_key(s, t, r, k) for s in range(6) for t in range(4) for r in (0, 7, 99) for k in (0, 1, 579)}
+    assert len(keys) == 6 * 4 * 3 * 3
+    c2 = W.config(2)
+    assert c2.wd_of(c2.params[0]) == 0.01 and c2.wd_of(c2.params[4]) == 0.0     # embedding decays, LayerNorm beta does not
+
+
+def _tensor(**kw):
+    base = dict(numel=4096, w_in=0x1000, m_in=0x10000, v_in=0x20000, w_out=0x30000, m_out=0x40000, v_out=0x50000,
+                w16_out=0x60000, grad=[0x70000, 0x80000], weight_decay=0.0)
+    base.update(kw)
+    return cc.Tensor(**base)
+
+
+@pytest.mark.parametrize("kw,R,code", [
+    (dict(w_in=0), 2, cc.CC_ERR_NULL),
+    (dict(w16_out=None), 2, cc.CC_ERR_NULL),
+    (dict(grad=[0x70000, 0]), 2, cc.CC_ERR_NULL),
+    (dict(m_in=0x10008), 2, cc.CC_ERR_ALIGN),
+    (dict(grad=[0x70002, 0x80000]), 2, cc.CC_ERR_ALIGN),
+    (dict(w_out=0x1000 + 64), 2, cc.CC_ERR_ALIAS),
+    (dict(), 0, cc.CC_ERR_ARG),
+    (dict(), 17, cc.CC_ERR_ARG),
+    (dict(weight_decay=float("nan")), 2, cc.CC_ERR_ARG),
+])
+def test_plan_create_rejects_bad_arguments_on_the_host(kw, R, code):
+    with pytest.raises(cc.CcError) as e:
+        cc.cc_plan_create([_tensor(**kw)], R)
+    assert e.value.code == code
+    assert cc.cc_last_error()
+
+
+def test_plan_create_rejects_empty_list_and_bad_chunk():
+    with pytest.raises(cc.CcError) as e:
+        cc.cc_plan_create([], 2)
+    assert e.value.code == cc.CC_ERR_ARG
+    with pytest.raises(cc.CcError) as e:
+        cc.cc_plan_create([_tensor()], 2, chunk_elems=1000)
+    assert e.value.code == cc.CC_ERR_ARG
+
+
+def test_step_calls_reject_null_plan_and_bad_copy_arguments():
+    lib = cc.load()
+    hp = cc.Hyper().to_c()
+    for name in ("cc_fused_adam_step", "cc_fused_lamb_step", "cc_unfused_adam_step", "cc_unfused_lamb_step",
+                 "cc_fused_lamb_phase1", "cc_fused_lamb_phase2"):
+        assert getattr(lib, name)(None, C.byref(hp), 0x1000, None) == cc.CC_ERR_NULL
+    assert lib.cc_copy_probe(None, 0x1000, 16, None) == cc.CC_ERR_NULL
+    assert lib.cc_copy_probe(0x1000, 0x2000, 17, None) == cc.CC_ERR_ARG
+    assert lib.cc_copy_probe(0x1008, 0x2000, 32, None) == cc.CC_ERR_ALIGN
+    assert lib.cc_plan_destroy(None) == cc.CC_OK
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    monkeypatch.setattr(cc, "_lib", None)
+    monkeypatch.setattr(cc, "LIB_PATH", str(tmp_path / "absent.so"))
+    with pytest.raises(FileNotFoundError):
+        cc.cc_version()
