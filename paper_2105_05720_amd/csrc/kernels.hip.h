@@ -97,7 +97,17 @@ __device__ __forceinline__ void st4(gf32 p, f32x4 x) { __builtin_nontemporal_sto
 __device__ __forceinline__ f16x8 ld8h(gcu16 p) { return __builtin_nontemporal_load((const CCF_GLOBAL f16x8 *)p); }
 __device__ __forceinline__ void st8h(gu16 p, f16x8 x) { __builtin_nontemporal_store(x, (CCF_GLOBAL f16x8 *)p); }
 __device__ __forceinline__ float ldh(gcu16 p) { return (float)*(const CCF_GLOBAL _Float16 *)p; }
-__device__ __forceinline__ void sth(gu16 p, float x) { *(CCF_GLOBAL _Float16 *)p = (_Float16)x; }  // round to nearest even
+
+// fp32 -> fp16, round to nearest even, of the fp32 value as stored.  The empty asm pins x in a register so
+// that the compiler cannot merge the conversion with the fma that produced x into one mixed-precision fma
+// (v_fma_mixlo_f16 rounds the exact product-sum straight to fp16, which can differ from rounding the fp32
+// result by one fp16 ulp).
+__device__ __forceinline__ _Float16 to_half(float x)
+{
+    asm volatile("" : "+v"(x));
+    return (_Float16)x;
+}
+__device__ __forceinline__ void sth(gu16 p, float x) { *(CCF_GLOBAL _Float16 *)p = to_half(x); }
 
 // Where a workgroup works: resolves its chunk to a tensor and an element range.
 struct Where {
@@ -172,7 +182,7 @@ __device__ __forceinline__ void store8h(gu16 p, const float (&x)[kPack])
 {
     f16x8 h;
 #pragma unroll
-    for (int k = 0; k < kPack; ++k) h[k] = (_Float16)x[k];   // v_cvt_f16_f32: round to nearest even, subnormals kept
+    for (int k = 0; k < kPack; ++k) h[k] = to_half(x[k]);    // v_cvt_f16_f32: round to nearest even, subnormals kept
     st8h(p, h);
 }
 

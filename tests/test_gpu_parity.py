@@ -74,7 +74,8 @@ def test_adam_in_place_guard_mode():
 
 
 def test_adam_subnormal_range_gradients_and_extreme_weights():
-    """Gradients ~N(0, 1e-3) are mostly fp16 subnormals; weights span fp16 subnormal, normal and overflow."""
+    """Gradients ~N(0, 1e-3) put ~5 % of the values in the fp16 subnormal range, N(0, 3e-5) most of them;
+    weights span fp16 subnormal, normal and overflow."""
     numels = [30000, 4097]
     shard = Shard(numels, [0.01, 0.0], 8, align_elems=8)
     seeded_state(shard, 3)
@@ -89,11 +90,11 @@ def test_adam_subnormal_range_gradients_and_extreme_weights():
     ost = OracleState(shard, range(2))
     hps = [hyper_pair(step=t) for t in (1, 2)]
     run_steps(shard, ost, cc.cc_fused_adam_step, oracle.adam_step, hps, "adam subnormal",
-              lambda i: seeded_grads(shard, 30 + i, 1e-3))
+              lambda i: seeded_grads(shard, 30 + i, 1e-3 if i == 0 else 3e-5))
     bits = to_np_bits(shard.w16_of(0))
     assert ((bits & 0x7C00) == 0).any() and ((bits & 0x7FFF) == 0x7C00).any()   # subnormals and infinities were emitted
     g = to_np_bits(shard.grad_of(0, 0))
-    assert np.mean(((g & 0x7C00) == 0) & ((g & 0x3FF) != 0)) > 0.5                # inputs really were subnormal
+    assert np.mean(((g & 0x7C00) == 0) & ((g & 0x3FF) != 0)) > 0.9                # the last inputs really were subnormal
     shard.destroy()
 
 
