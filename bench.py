@@ -1,0 +1,239 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused reduce + optimizer step on one MI355X.
+
+A step is one fused reduce+Adam pass (chunk lookup, R-way fp16 reduce, unscale and overflow test, moments,
+weight update, fp16 emission) over the BERT-Large parameter list with R = 8 gradient slices (configuration 2),
+inputs resident in HBM.  The same run also times, with the same method, the fused LAMB step on that list
+(configuration 3), the unfused reduce / optimizer / cast pipelines, a plain copy kernel (the practical HBM
+ceiling) and the CPU oracle on a bounded sample.  One JSON line is printed.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--chunk-elems N] [--no-extras]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+
+
+def adam_bytes_per_param(R):   # read 2R (fp16 grads) + 12 (w, m, v); write 12 (w, m, v) + 2 (fp16 w)
+    return 2 * R + 26
+
+
+def lamb_bytes_per_param(R):   # phase 1: read 2R + 12, write 8; phase 2: read 12, write 6
+    return 2 * R + 38
+
+
+def unfused_adam_bytes_per_param(R):   # reduce: 2R + 4; optimizer: 16 + 12; cast: 4 + 2
+    return 2 * R + 38
+
+
+def unfused_lamb_bytes_per_param(R):   # reduce 2R + 4; phase 1: 16 + 8; phase 2: 12 + 4; cast 4 + 2
+    return 2 * R + 50
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=2, help="workload configuration 1..5 (default 2, the metric's)")
+    ap.add_argument("--chunk-elems", type=int, default=0)
+    ap.add_argument("--in-place", action="store_true", help="in-place state with the per-element guard (skip_mode 1)")
+    ap.add_argument("--no-extras", action="store_true", help="only the headline step (for profiling runs)")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    args = ap.parse_args()
+
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU's shard only (no collectives, no sharding across GPUs); "
+              "run it with --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+
+    from paper_2105_05720_amd import binding as cc
+    from paper_2105_05720_amd import workloads as W
+    from paper_2105_05720_amd.shard import Shard
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    cc.load()                                            # raises if libccfused.so is missing
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    cfg = W.config(args.config)
+    R, N = cfg.R, cfg.numel
+    K, Wm = args.steps, args.warmup
+
+    shard = Shard([s.numel for s in cfg.params], [cfg.wd_of(s) for s in cfg.params], R, device=dev,
+                  chunk_elems=args.chunk_elems, in_place=args.in_place)
+    W.fill_state(shard, cfg)
+    W.fill_grads(shard, cfg, 1)
+    torch.cuda.synchronize()
+    _, chunks, table_bytes = cc.cc_plan_info(shard.plans[0])
+    skip_mode = 1 if args.in_place else 0
+
+    def hyper(t):
+        return cc.Hyper(lr=cfg.lr, beta1=cfg.beta1, beta2=cfg.beta2, eps=cfg.eps, loss_scale=cfg.loss_scale, step=t,
+                        skip_mode=skip_mode)
+
+    def timed(step_fn, steps, warmup, t0=1):
+        """warmup + steps consecutive optimizer steps, each reading the copy the previous one wrote; HIP events
+        on the launch stream bracket exactly `steps` of them.  Returns (ms per step, flag seen at the end)."""
+        t = t0
+        for _ in range(warmup):
+            shard.run(step_fn, hyper(t))
+            shard.commit()
+            t += 1
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            shard.run(step_fn, hyper(t))
+            shard.commit()
+            t += 1
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / steps, int(shard.flag.item()), t
+
+    headline_fn = cc.cc_fused_adam_step if cfg.optimizer == "adam" else cc.cc_fused_lamb_step
+    bpp = adam_bytes_per_param(R) if cfg.optimizer == "adam" else lamb_bytes_per_param(R)
+
+    # ---- the K timed steps of the headline path -------------------------------------------------------------
+    torch.cuda.synchronize()
+    wall0 = time.perf_counter()
+    ms, flag, t_next = timed(headline_fn, K, Wm)
+    wall = time.perf_counter() - wall0
+    assert flag == 0, "overflow flag set during the timed run"
+    gbs = bpp * N / (ms * 1e-3) / 1e9
+    out = {
+        "metric": "fused reduce+optimizer HBM GB/s (% of MI355X peak) and params updated/sec",
+        "value": round(gbs, 1), "unit": "GB/s",
+        "pct_of_peak": round(100 * gbs / HBM_PEAK_GBS, 2),
+        "params_per_sec": round(N / (ms * 1e-3), 1),
+        "n_gpus": 1, "steps": K, "warmup": Wm, "ms_per_step": round(ms, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "config %d: fused %s, %s, T=%d tensors, N=%d fp32 params, R=%d fp16 gradient slices, "
+                               "%s state" % (cfg.index, cfg.optimizer,
+                                             {1: "one flat tensor", 2: "BERT-Large parameter list", 3: "BERT-Large parameter list",
+                                              4: "GPT-2 1.5B parameter list", 5: "1/8 shard of an 8.3B transformer"}[cfg.index],
+                                             len(cfg.params), N, R, "in-place" if args.in_place else "out-of-place (ping-pong)"),
+                   "chunk_elems": args.chunk_elems or cc.cc_default_chunk_elems(), "chunks": chunks,
+                   "table_bytes": table_bytes, "algorithmic_bytes_per_param": bpp},
+        "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                     "kernel": "fused_adam_kernel<R=%d>" % R if cfg.optimizer == "adam" else "lamb_phase1_kernel + lamb_phase2_kernel",
+                     "bytes_per_launch": bpp * N, "avg_launch_ms": round(ms, 5)},
+    }
+
+    if not args.no_extras:
+        extras = {}
+        # the same K steps with the flag read back (and the commit decided) after every step
+        for _ in range(3):
+            shard.step(headline_fn, hyper(t_next)); t_next += 1
+        torch.cuda.synchronize()
+        w0 = time.perf_counter()
+        for _ in range(K):
+            assert shard.step(headline_fn, hyper(t_next)) == 0
+            t_next += 1
+        extras["ms_per_step_with_flag_readback"] = round((time.perf_counter() - w0) * 1e3 / K, 5)
+        extras["wall_ms_per_step_enqueue_only_loop"] = round(wall * 1e3 / (K + Wm), 5)
+
+        def rate(fn, bytes_pp, steps):
+            m, f, _ = timed(fn, steps, max(2, Wm // 2), t0=t_next)
+            assert f == 0
+            return {"ms_per_step": round(m, 5), "GB/s": round(bytes_pp * N / (m * 1e-3) / 1e9, 1),
+                    "params_per_sec": round(N / (m * 1e-3), 1), "algorithmic_bytes_per_param": bytes_pp}
+        ks = max(5, K // 4)
+        if cfg.optimizer == "adam":
+            extras["fused_lamb_same_list"] = rate(cc.cc_fused_lamb_step, lamb_bytes_per_param(R), ks) if not args.in_place else None
+        else:
+            extras["fused_adam_same_list"] = rate(cc.cc_fused_adam_step, adam_bytes_per_param(R), ks)
+        extras["unfused_adam"] = rate(cc.cc_unfused_adam_step, unfused_adam_bytes_per_param(R), ks)
+        if not args.in_place:
+            extras["unfused_lamb"] = rate(cc.cc_unfused_lamb_step, unfused_lamb_bytes_per_param(R), ks)
+        fa = extras.get("fused_adam_same_list", {"ms_per_step": ms})["ms_per_step"] if cfg.optimizer != "adam" else ms
+        extras["fused_vs_unfused_adam_speedup"] = round(extras["unfused_adam"]["ms_per_step"] / fa, 3)
+
+        # plain copy kernel: the practical streaming ceiling of this machine (bytes counted once read + once written)
+        nbytes = 2 << 30
+        src = torch.empty(nbytes, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        for _ in range(3):
+            cc.cc_copy_probe(dst, src, nbytes)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(20):
+            cc.cc_copy_probe(dst, src, nbytes)
+        e1.record()
+        torch.cuda.synchronize()
+        extras["copy_kernel_GB/s"] = round(2 * nbytes / (e0.elapsed_time(e1) / 20 * 1e-3) / 1e9, 1)
+        del src, dst
+        out["extras"] = extras
+
+        out["cpu_baseline"] = cpu_baseline(shard, cfg, hyper(1), args.cpu_seconds)
+
+    shard.destroy()
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+def cpu_baseline(shard, cfg, ghp, target_seconds):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload: the first tensors of the list up to
+    a parameter budget sized from a short calibration run, all host threads (whole tensors per thread)."""
+    import numpy as np
+
+    import oracle
+
+    threads = min(16, len(os.sched_getaffinity(0)))
+    step_fn = oracle.adam_step if cfg.optimizer == "adam" else oracle.lamb_step
+    ohp = oracle.Hyper(lr=ghp.lr, beta1=ghp.beta1, beta2=ghp.beta2, eps=ghp.eps, loss_scale=ghp.loss_scale, step=1)
+    bits = lambda t: t.cpu().view(__import__("torch").int16).numpy().view(np.uint16).copy()
+
+    def tensors_of(ks):
+        return [oracle.OracleTensor(w=shard.w_of(k).cpu().numpy().copy(), m=shard.m_of(k).cpu().numpy().copy(),
+                                    v=shard.v_of(k).cpu().numpy().copy(),
+                                    grads=[bits(shard.grad_of(r, k)) for r in range(cfg.R)],
+                                    weight_decay=shard.wds[k]) for k in ks]
+
+    # sample: tensors of about equal size so that threads stay busy; skip the giant embeddings
+    order = [k for k, s in enumerate(cfg.params) if 0 < s.numel <= 8_000_000] or list(range(len(cfg.params)))
+    calib = []
+    budget = 2_000_000
+    for k in order:
+        calib.append(k)
+        budget -= cfg.params[k].numel
+        if budget <= 0:
+            break
+    ots = tensors_of(calib)
+    t0 = time.perf_counter()
+    step_fn(ots, ohp, threads=threads)
+    rate = sum(cfg.params[k].numel for k in calib) / (time.perf_counter() - t0)
+    want = rate * target_seconds
+    sample, total = [], 0
+    for k in order:
+        sample.append(k)
+        total += cfg.params[k].numel
+        if total >= want:
+            break
+    ots = tensors_of(sample)
+    t0 = time.perf_counter()
+    step_fn(ots, ohp, threads=threads)
+    dt = time.perf_counter() - t0
+    bpp = adam_bytes_per_param(cfg.R) if cfg.optimizer == "adam" else lamb_bytes_per_param(cfg.R)
+    return {"value": round(bpp * total / dt / 1e9, 4), "unit": "GB/s", "params_per_sec": round(total / dt, 1),
+            "cores": threads, "kind": "oracle", "seconds": round(dt, 2),
+            "sample": "first %d tensors (<= 8M elements each) of the same list, %d params, one %s step" % (len(sample), total, cfg.optimizer)}
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -192,3 +192,26 @@ def aligned_offsets(numels, align_elems: int) -> Tuple[List[int], int]:
 def table_bytes_paper(n: int) -> int:
     """Memory of the paper's bucket table for one tensor of n elements (Section 5.4): 12 B per 2^10 elements."""
     return 12 * (-(-n // 1024))
+
+
+# ---- filling a device shard (any object with w_of/m_of/v_of/w16_of/grad_of(k) views) with a config's bits ----
+
+def fill_state(shard, cfg: Config) -> None:
+    """Initial committed state of a config: seeded weights, m = v = 0, fp16 copy of the weights."""
+    for k, spec in enumerate(cfg.params):
+        init_weight(spec, cfg.seed, k, shard.device, out=shard.w_of(k))
+        shard.m_of(k).zero_()
+        shard.v_of(k).zero_()
+        shard.w16_of(k).copy_(shard.w_of(k))
+
+
+def fill_grads(shard, cfg: Config, call_index: int) -> None:
+    """The R gradient slices of one optimizer call.  call_index counts calls from 1 (a skipped step consumes
+    an index too, so a repeated step draws fresh gradients).  Config 4 plants its +inf in call 2."""
+    for k, spec in enumerate(cfg.params):
+        for r in range(cfg.R):
+            grad_slice(spec.numel, cfg.grad_std, cfg.seed, call_index, r, k, shard.device, out=shard.grad_of(r, k))
+    if cfg.index == 4 and call_index == CFG4_INF_STEP:
+        k = [s.name for s in cfg.params].index(CFG4_INF_TENSOR)
+        # 0x7C00 as a signed 16-bit pattern
+        shard.grad_of(CFG4_INF_RANK, k).view(torch.int16)[CFG4_INF_INDEX] = HALF_POS_INF
