@@ -17,6 +17,8 @@ using namespace ccf;
 namespace {
 
 constexpr int32_t kDefaultChunkElems = 4096;
+constexpr int32_t kMaxChunkElems = 1 << 24;     // lane offsets inside a chunk are 32-bit byte offsets
+constexpr int kBlock = 256;                      // threads per workgroup of the streaming kernels
 
 thread_local char g_err[512] = "";
 
@@ -38,7 +40,7 @@ int fail(cc_status code, const char *fmt, ...)
 int32_t resolve_chunk(int32_t chunk_elems)
 {
     if (chunk_elems == 0) return kDefaultChunkElems;
-    if (chunk_elems < 0 || chunk_elems % 1024 != 0) return -1;
+    if (chunk_elems < 0 || chunk_elems % 1024 != 0 || chunk_elems > kMaxChunkElems) return -1;
     return chunk_elems;
 }
 
@@ -81,7 +83,7 @@ int64_t cc_chunk_count(const uint64_t *numels, int32_t T, int32_t chunk_elems)
     if (!numels && T > 0) return fail(CC_ERR_NULL, "cc_chunk_count: numels is NULL");
     if (T < 0) return fail(CC_ERR_ARG, "cc_chunk_count: T = %d", T);
     const int32_t ce = resolve_chunk(chunk_elems);
-    if (ce < 0) return fail(CC_ERR_ARG, "chunk_elems = %d is not a positive multiple of 1024", chunk_elems);
+    if (ce < 0) return fail(CC_ERR_ARG, "chunk_elems = %d is not a positive multiple of 1024 up to 2^24", chunk_elems);
     int64_t total = 0;
     for (int32_t t = 0; t < T; ++t) {
         const uint64_t c = (numels[t] + (uint64_t)ce - 1) / (uint64_t)ce;
@@ -118,7 +120,7 @@ int cc_plan_create(const cc_tensor *tensors, int32_t T, int32_t R, int32_t chunk
     if (T <= 0) return fail(CC_ERR_ARG, "cc_plan_create: T = %d must be positive", T);
     if (R < 1 || R > CC_MAX_R) return fail(CC_ERR_ARG, "cc_plan_create: R = %d outside 1..%d", R, CC_MAX_R);
     const int32_t ce = resolve_chunk(chunk_elems);
-    if (ce < 0) return fail(CC_ERR_ARG, "chunk_elems = %d is not a positive multiple of 1024", chunk_elems);
+    if (ce < 0) return fail(CC_ERR_ARG, "chunk_elems = %d is not a positive multiple of 1024 up to 2^24", chunk_elems);
 
     bool in_place = false;
     std::vector<uint64_t> numels((size_t)T);
@@ -299,7 +301,7 @@ void launch_fused_adam(const cc_plan *p, const StepScalars &s, int32_t *flag, hi
 {
     const dim3 grid((unsigned)p->chunks), block(kBlock);
     switch (p->R) {
-#define CASE(r) case r: hipLaunchKernelGGL((fused_adam_kernel<r, MODE>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag); break;
+#define CASE(r) case r: hipLaunchKernelGGL((fused_adam_kernel<r, MODE, kBlock>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag); break;
         FOR_EACH_R(CASE)
 #undef CASE
     }
@@ -309,7 +311,7 @@ void launch_lamb_phase1(const cc_plan *p, const StepScalars &s, int32_t *flag, h
 {
     const dim3 grid((unsigned)p->chunks), block(kBlock);
     switch (p->R) {
-#define CASE(r) case r: hipLaunchKernelGGL((lamb_phase1_kernel<r, false>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, p->d_partials, flag); break;
+#define CASE(r) case r: hipLaunchKernelGGL((lamb_phase1_kernel<r, kBlock>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, p->d_partials, flag); break;
         FOR_EACH_R(CASE)
 #undef CASE
     }
@@ -319,7 +321,7 @@ void launch_reduce(const cc_plan *p, const StepScalars &s, int32_t *flag, hipStr
 {
     const dim3 grid((unsigned)p->chunks), block(kBlock);
     switch (p->R) {
-#define CASE(r) case r: hipLaunchKernelGGL((reduce_kernel<r>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag); break;
+#define CASE(r) case r: hipLaunchKernelGGL((reduce_kernel<r, kBlock>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag); break;
         FOR_EACH_R(CASE)
 #undef CASE
     }
@@ -336,14 +338,14 @@ int lamb_phase2_impl(cc_plan *p, const StepScalars &s, const int32_t *flag, hipS
 {
     if (p->chunks == 0) return CC_OK;
     const dim3 grid((unsigned)p->chunks), block(kBlock);
-    if (emit16) hipLaunchKernelGGL((lamb_phase2_kernel<true>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, p->d_sums, flag);
-    else hipLaunchKernelGGL((lamb_phase2_kernel<false>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, p->d_sums, flag);
+    if (emit16) hipLaunchKernelGGL((lamb_phase2_kernel<true, kBlock>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, p->d_sums, flag);
+    else hipLaunchKernelGGL((lamb_phase2_kernel<false, kBlock>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, p->d_sums, flag);
     return launched("lamb_phase2_kernel");
 }
 
 int lamb_norms(cc_plan *p, hipStream_t st)
 {
-    hipLaunchKernelGGL(lamb_norms_kernel, dim3((unsigned)p->T), dim3(kBlock), 0, st, p->d_tensors, p->d_partials, p->d_sums);
+    hipLaunchKernelGGL(lamb_norms_kernel, dim3((unsigned)p->T), dim3(kNormBlock), 0, st, p->d_tensors, p->d_partials, p->d_sums);
     return launched("lamb_norms_kernel");
 }
 
@@ -412,13 +414,13 @@ int cc_unfused_adam_step(cc_plan *p, const cc_hparams *hp, int32_t *flag, void *
     if ((rc = launched("reduce_kernel"))) return rc;
     const int mode = (hp->skip_mode == 1 ? kModeGuard : 0) | (hp->adam_mode == 0 ? kModeL2 : 0);
     switch (mode) {
-        case 0: hipLaunchKernelGGL((adam_from_sum_kernel<0>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag); break;
-        case 1: hipLaunchKernelGGL((adam_from_sum_kernel<1>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag); break;
-        case 2: hipLaunchKernelGGL((adam_from_sum_kernel<2>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag); break;
-        default: hipLaunchKernelGGL((adam_from_sum_kernel<3>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag); break;
+        case 0: hipLaunchKernelGGL((adam_from_sum_kernel<0, kBlock>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag); break;
+        case 1: hipLaunchKernelGGL((adam_from_sum_kernel<1, kBlock>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag); break;
+        case 2: hipLaunchKernelGGL((adam_from_sum_kernel<2, kBlock>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag); break;
+        default: hipLaunchKernelGGL((adam_from_sum_kernel<3, kBlock>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag); break;
     }
     if ((rc = launched("adam_from_sum_kernel"))) return rc;
-    hipLaunchKernelGGL(cast_kernel, grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag, hp->skip_mode == 0 ? 1 : 0);
+    hipLaunchKernelGGL((cast_kernel<kBlock>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag, hp->skip_mode == 0 ? 1 : 0);
     return launched("cast_kernel");
 }
 
@@ -434,14 +436,14 @@ int cc_unfused_lamb_step(cc_plan *p, const cc_hparams *hp, int32_t *flag, void *
         const dim3 grid((unsigned)p->chunks), block(kBlock);
         launch_reduce(p, s, flag, st);
         if ((rc = launched("reduce_kernel"))) return rc;
-        hipLaunchKernelGGL((lamb_phase1_kernel<1, true>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, p->d_partials, flag);
+        hipLaunchKernelGGL((lamb_phase1_from_sum_kernel<kBlock>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, p->d_partials, flag);
         if ((rc = launched("lamb_phase1_kernel"))) return rc;
     }
     if ((rc = lamb_norms(p, st))) return rc;
     if ((rc = lamb_phase2_impl(p, s, flag, st, false))) return rc;
     if (p->chunks > 0) {
         const dim3 grid((unsigned)p->chunks), block(kBlock);
-        hipLaunchKernelGGL(cast_kernel, grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag, 1);
+        hipLaunchKernelGGL((cast_kernel<kBlock>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag, 1);
         return launched("cast_kernel");
     }
     return CC_OK;
@@ -454,10 +456,10 @@ int cc_copy_probe(void *dst, const void *src, uint64_t bytes, void *stream)
     if (misaligned(dst) || misaligned(src)) return fail(CC_ERR_ALIGN, "cc_copy_probe: pointers must be 16-byte aligned");
     if (bytes == 0) return CC_OK;
     const uint64_t n16 = bytes / 16;
-    const uint64_t per_block = (uint64_t)kBlock * 4;
+    const uint64_t per_block = (uint64_t)kCopyBlock * 4;
     const uint64_t blocks = (n16 + per_block - 1) / per_block;
     if (blocks > 0x7fffffffull) return fail(CC_ERR_ARG, "cc_copy_probe: too large for one launch");
-    hipLaunchKernelGGL(copy_kernel, dim3((unsigned)blocks), dim3(kBlock), 0, (hipStream_t)stream, (u32x4 *)dst, (const u32x4 *)src, n16);
+    hipLaunchKernelGGL(copy_kernel, dim3((unsigned)blocks), dim3(kCopyBlock), 0, (hipStream_t)stream, (u32x4 *)dst, (const u32x4 *)src, n16);
     return launched("copy_kernel");
 }
 

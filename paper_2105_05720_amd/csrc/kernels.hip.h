@@ -1,12 +1,21 @@
-// Device side of ccfused: streaming kernels for gfx950 (wave64, 128-bit global accesses).
+// Device side of ccfused: streaming kernels for gfx950 (wave64).
 //
-// Every kernel here is bound by HBM bandwidth: per parameter it moves 2R bytes of fp16 gradients and
-// 26 bytes of fp32/fp16 state against ~R + 30 scalar flops, so there is no contraction and no MFMA.
-// The shape follows from that: one workgroup per chunk of one tensor (the chunk table replaces the
-// per-thread tensor search of Section 5.4), every lane owns 8 consecutive elements per sweep so that
-// one fp16 slice is one 16-byte load and each fp32 array is two, all loads of a sweep are issued before
-// the first use, and results leave through 16-byte stores.  The reduced gradient stays in registers
-// (Section 3.3, AllReduce Fuse: the output of the reduction is handed to the computation directly).
+// Every kernel here is bound by HBM bandwidth: per parameter the fused Adam step moves 2R bytes of fp16
+// gradients and 26 bytes of fp32/fp16 state against ~R + 30 scalar flops, so there is no contraction and no
+// MFMA.  The shape follows from what the memory system rewards:
+//
+//   * One workgroup per chunk of one tensor; the chunk table replaces a per-thread search over the scattered
+//     tensors (Section 5.4).  The table entry and the tensor descriptor are uniform, so they arrive through
+//     scalar loads and every buffer is addressed as scalar base + 32-bit lane offset.
+//   * Ownership is chosen so that EVERY access instruction of a wave covers one contiguous span: a lane owns
+//     4 consecutive elements per group, i.e. one 16-byte access per fp32 array (1 KiB per wave instruction)
+//     and one 8-byte access per fp16 array (512 B per wave instruction).  Letting a lane own 8 consecutive
+//     elements instead would split each fp32 row of a wave into two half-filled store instructions, and HBM
+//     pays dearly for partially written lines (measured: 2.5 TB/s against 5.8 TB/s for the stores alone).
+//   * Two groups per sweep, all loads of both groups issued before the first use, so that each wave keeps
+//     2 x (R + 3) independent requests in flight.
+//   * The reduced gradient stays in registers (Section 3.3, AllReduce Fuse: the output of the reduction is
+//     handed to the computation directly, never through memory).
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -16,15 +25,13 @@
 
 namespace ccf {
 
-constexpr int kBlock = 256;            // 4 waves
-constexpr int kPack = 8;               // elements per lane per sweep
-constexpr int kSweep = kBlock * kPack; // elements one workgroup covers per sweep
+constexpr int kLanePack = 4;           // consecutive elements a lane owns per group
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-// One tensor of the shard as the kernels see it.  Read through scalar loads: the index is uniform.
+// One tensor of the shard as the kernels see it.
 struct DevTensor {
     uint64_t numel;
     const float *w_in, *m_in, *v_in;
@@ -58,7 +65,7 @@ enum : int { kModeGuard = 1, kModeL2 = 2 };
 
 __device__ __forceinline__ bool not_finite(float x) { return !(__builtin_fabsf(x) <= 3.402823466e+38f); }
 
-// Moments of one element from the reduced sum S (Fig. 4a, second and third statement).
+// Moments of one element from the reduced sum S (Fig. 4a: the m and v updates).
 template <int MODE>
 __device__ __forceinline__ void moments(float S, float w, float wd, const StepScalars &s, float &m, float &v)
 {
@@ -68,7 +75,7 @@ __device__ __forceinline__ void moments(float S, float w, float wd, const StepSc
     v = __builtin_fmaf(s.beta2, v, (s.omb2 * g) * g);
 }
 
-// Update direction u from the new moments (Fig. 4a, bias corrections and the quotient), plus decoupled decay.
+// Update direction u from the new moments (Fig. 4a: bias corrections and the quotient), plus decoupled decay.
 template <int MODE>
 __device__ __forceinline__ float direction(float w, float wd, float m, float v, const StepScalars &s)
 {
@@ -79,24 +86,22 @@ __device__ __forceinline__ float direction(float w, float wd, float m, float v, 
     return u;
 }
 
-// Pointers read from a descriptor are generic; every buffer here is device memory, so address it as global
-// (global_load/global_store instead of flat accesses, which also have to test for the LDS aperture).
+// ---- memory access: every buffer is device memory, addressed as uniform base + 32-bit byte offset ----------
 #define CCF_GLOBAL __attribute__((address_space(1)))
-typedef const CCF_GLOBAL float *gcf32;
-typedef CCF_GLOBAL float *gf32;
-typedef const CCF_GLOBAL uint16_t *gcu16;
-typedef CCF_GLOBAL uint16_t *gu16;
+typedef const CCF_GLOBAL char *gcbytes;
+typedef CCF_GLOBAL char *gbytes;
 
-__device__ __forceinline__ gcf32 as_global(const float *p) { return (gcf32)p; }
-__device__ __forceinline__ gf32 as_global(float *p) { return (gf32)p; }
-__device__ __forceinline__ gcu16 as_global(const uint16_t *p) { return (gcu16)p; }
-__device__ __forceinline__ gu16 as_global(uint16_t *p) { return (gu16)p; }
+// Base of a chunk inside one of a tensor's arrays (generic pointers from the descriptor become global ones).
+__device__ __forceinline__ gcbytes chunk_base(const void *p, uint64_t byte_off) { return (gcbytes)p + byte_off; }
+__device__ __forceinline__ gbytes chunk_base(void *p, uint64_t byte_off) { return (gbytes)p + byte_off; }
 
-__device__ __forceinline__ f32x4 ld4(gcf32 p) { return __builtin_nontemporal_load((const CCF_GLOBAL f32x4 *)p); }
-__device__ __forceinline__ void st4(gf32 p, f32x4 x) { __builtin_nontemporal_store(x, (CCF_GLOBAL f32x4 *)p); }
-__device__ __forceinline__ f16x8 ld8h(gcu16 p) { return __builtin_nontemporal_load((const CCF_GLOBAL f16x8 *)p); }
-__device__ __forceinline__ void st8h(gu16 p, f16x8 x) { __builtin_nontemporal_store(x, (CCF_GLOBAL f16x8 *)p); }
-__device__ __forceinline__ float ldh(gcu16 p) { return (float)*(const CCF_GLOBAL _Float16 *)p; }
+__device__ __forceinline__ f32x4 ld_f32x4(gcbytes b, uint32_t off) { return __builtin_nontemporal_load((const CCF_GLOBAL f32x4 *)(b + off)); }
+__device__ __forceinline__ f16x4 ld_f16x4(gcbytes b, uint32_t off) { return __builtin_nontemporal_load((const CCF_GLOBAL f16x4 *)(b + off)); }
+__device__ __forceinline__ void st_f32x4(gbytes b, uint32_t off, f32x4 x) { __builtin_nontemporal_store(x, (CCF_GLOBAL f32x4 *)(b + off)); }
+__device__ __forceinline__ void st_f16x4(gbytes b, uint32_t off, f16x4 x) { __builtin_nontemporal_store(x, (CCF_GLOBAL f16x4 *)(b + off)); }
+__device__ __forceinline__ float ld_f32(gcbytes b, uint32_t off) { return *(const CCF_GLOBAL float *)(b + off); }
+__device__ __forceinline__ float ld_f16(gcbytes b, uint32_t off) { return (float)*(const CCF_GLOBAL _Float16 *)(b + off); }
+__device__ __forceinline__ void st_f32(gbytes b, uint32_t off, float x) { *(CCF_GLOBAL float *)(b + off) = x; }
 
 // fp32 -> fp16, round to nearest even, of the fp32 value as stored.  The empty asm pins x in a register so
 // that the compiler cannot merge the conversion with the fma that produced x into one mixed-precision fma
@@ -107,9 +112,20 @@ __device__ __forceinline__ _Float16 to_half(float x)
     asm volatile("" : "+v"(x));
     return (_Float16)x;
 }
-__device__ __forceinline__ void sth(gu16 p, float x) { *(CCF_GLOBAL _Float16 *)p = to_half(x); }
+__device__ __forceinline__ void st_f16(gbytes b, uint32_t off, float x) { *(CCF_GLOBAL _Float16 *)(b + off) = to_half(x); }
 
-// Where a workgroup works: resolves its chunk to a tensor and an element range.
+__device__ __forceinline__ void ld_f32x4(gcbytes b, uint32_t off, float (&x)[4])
+{
+    const f32x4 t = ld_f32x4(b, off);
+    x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w;
+}
+__device__ __forceinline__ void st_f32x4(gbytes b, uint32_t off, const float (&x)[4]) { st_f32x4(b, off, f32x4{x[0], x[1], x[2], x[3]}); }
+__device__ __forceinline__ void st_f16x4(gbytes b, uint32_t off, const float (&x)[4])
+{
+    st_f16x4(b, off, f16x4{to_half(x[0]), to_half(x[1]), to_half(x[2]), to_half(x[3])});
+}
+
+// ---- where a workgroup works -----------------------------------------------------------------------------------
 struct Where {
     const DevTensor *t;
     uint32_t tensor;          // index of t in the plan's tensor list
@@ -139,122 +155,179 @@ __device__ __forceinline__ void raise_flag(bool bad, int32_t *flag)
 
 __global__ void clear_flag_kernel(int32_t *flag) { *flag = 0; }
 
-// Sum of the R slices for the 8 elements at p[r] + i, fixed rank order, fp32.
-template <int R>
-__device__ __forceinline__ void load_grads(const gcu16 *gp, uint32_t i, f16x8 (&g)[R])
+// ---- the streaming skeleton --------------------------------------------------------------------------------------
+// An Op describes one kernel's per-element work:
+//   struct Regs;                                   registers of one group (4 elements of this lane)
+//   void load(Regs&, uint32_t e) const;            vector loads of elements e .. e+3 of the chunk
+//   void compute(Regs&);                           arithmetic on the group
+//   void store(const Regs&, uint32_t e) const;     vector stores
+//   void single(uint32_t j);                       one element, scalar accesses (ragged end of a tensor)
+// A sweep is two groups BLOCK*4 elements apart.  A full sweep issues the loads of both groups, then computes
+// and stores; the ragged end of a chunk (only a tensor's last chunk has one) falls back group by group.
+template <int BLOCK, class Op>
+__device__ __forceinline__ void stream_chunk(Op &op, uint32_t len)
 {
-#pragma unroll
-    for (int r = 0; r < R; ++r) g[r] = ld8h(gp[r] + i);
-}
-
-template <int R>
-__device__ __forceinline__ void reduce_grads(const f16x8 (&g)[R], float (&S)[kPack])
-{
-#pragma unroll
-    for (int k = 0; k < kPack; ++k) S[k] = (float)g[0][k];
-#pragma unroll
-    for (int r = 1; r < R; ++r)
-#pragma unroll
-        for (int k = 0; k < kPack; ++k) S[k] += (float)g[r][k];
-}
-
-template <int R>
-__device__ __forceinline__ float reduce_one(const gcu16 *gp, uint32_t j)
-{
-    float S = ldh(gp[0] + j);
-#pragma unroll
-    for (int r = 1; r < R; ++r) S += ldh(gp[r] + j);
-    return S;
-}
-
-__device__ __forceinline__ void unpack(const f32x4 &a, const f32x4 &b, float (&x)[kPack])
-{
-    x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w; x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
-}
-
-__device__ __forceinline__ void store8(gf32 p, const float (&x)[kPack])
-{
-    st4(p, f32x4{x[0], x[1], x[2], x[3]});
-    st4(p + 4, f32x4{x[4], x[5], x[6], x[7]});
-}
-
-__device__ __forceinline__ void store8h(gu16 p, const float (&x)[kPack])
-{
-    f16x8 h;
-#pragma unroll
-    for (int k = 0; k < kPack; ++k) h[k] = to_half(x[k]);    // v_cvt_f16_f32: round to nearest even, subnormals kept
-    st8h(p, h);
-}
-
-// ---------------------------------------------------------------------------------------------------
-// Fused reduce + Adam + fp16 emission: one pass, 2R + 26 bytes per parameter.
-// ---------------------------------------------------------------------------------------------------
-template <int R, int MODE>
-__global__ __launch_bounds__(kBlock) void fused_adam_kernel(const DevTensor *__restrict__ tensors,
-                                                            const Chunk *__restrict__ chunks, StepScalars s,
-                                                            int32_t *__restrict__ flag)
-{
-    const Where wh = locate(tensors, chunks, s.chunk_elems);
-    const DevTensor *t = wh.t;
-    const float wd = t->wd;
-    gcu16 gp[R];
-#pragma unroll
-    for (int r = 0; r < R; ++r) gp[r] = as_global(t->grad[r]) + wh.base;
-    const gcf32 w_in = as_global(t->w_in) + wh.base, m_in = as_global(t->m_in) + wh.base, v_in = as_global(t->v_in) + wh.base;
-    const gf32 w_out = as_global(t->w_out) + wh.base, m_out = as_global(t->m_out) + wh.base, v_out = as_global(t->v_out) + wh.base;
-    const gu16 w16 = as_global(t->w16) + wh.base;
-
-    bool bad = false;
-    for (uint32_t i = threadIdx.x * kPack; i < wh.len; i += kSweep) {
-        if (i + kPack <= wh.len) {
-            f16x8 g[R];
-            load_grads<R>(gp, i, g);
-            const f32x4 w0 = ld4(w_in + i), w1 = ld4(w_in + i + 4);
-            const f32x4 m0 = ld4(m_in + i), m1 = ld4(m_in + i + 4);
-            const f32x4 v0 = ld4(v_in + i), v1 = ld4(v_in + i + 4);
-            float S[kPack], w[kPack], m[kPack], v[kPack];
-            reduce_grads<R>(g, S);
-            unpack(w0, w1, w);
-            unpack(m0, m1, m);
-            unpack(v0, v1, v);
-#pragma unroll
-            for (int k = 0; k < kPack; ++k) {
-                const bool nf = not_finite(S[k]);
-                bad |= nf;
-                float mk = m[k], vk = v[k];
-                moments<MODE>(S[k], w[k], wd, s, mk, vk);
-                const float u = direction<MODE>(w[k], wd, mk, vk, s);
-                const float wk = __builtin_fmaf(-s.lr, u, w[k]);
-                if (!(MODE & kModeGuard) || !nf) { m[k] = mk; v[k] = vk; w[k] = wk; }
-            }
-            store8(m_out + i, m);
-            store8(v_out + i, v);
-            store8(w_out + i, w);
-            store8h(w16 + i, w);
+    constexpr uint32_t kGroup = BLOCK * kLanePack;
+    constexpr uint32_t kSweep = 2 * kGroup;
+    const uint32_t lane_e = threadIdx.x * kLanePack;
+    uint32_t s0 = 0;
+    for (; s0 + kSweep <= len; s0 += kSweep) {
+        typename Op::Regs a, b;
+        op.load(a, s0 + lane_e);
+        op.load(b, s0 + kGroup + lane_e);
+        __builtin_amdgcn_sched_barrier(0);         // keep all loads of the sweep ahead of the first use
+        op.compute(a);
+        op.store(a, s0 + lane_e);
+        op.compute(b);
+        op.store(b, s0 + kGroup + lane_e);
+    }
+    for (uint32_t e = s0 + lane_e; e < len; e += kGroup) {
+        if (e + kLanePack <= len) {
+            typename Op::Regs a;
+            op.load(a, e);
+            op.compute(a);
+            op.store(a, e);
         } else {
-            for (uint32_t j = i; j < wh.len; ++j) {
-                const float S = reduce_one<R>(gp, j);
-                const bool nf = not_finite(S);
-                bad |= nf;
-                const float w = w_in[j];
-                float m = m_in[j], v = v_in[j];
-                float wn = w;
-                if (!(MODE & kModeGuard) || !nf) {
-                    moments<MODE>(S, w, wd, s, m, v);
-                    wn = __builtin_fmaf(-s.lr, direction<MODE>(w, wd, m, v, s), w);
-                }
-                m_out[j] = m;
-                v_out[j] = v;
-                w_out[j] = wn;
-                sth(w16 + j, wn);
-            }
+            for (uint32_t j = e; j < len; ++j) op.single(j);
         }
     }
-    raise_flag(bad, flag);
+}
+
+// Sum of the R slices for 4 elements, fixed rank order, fp32 (fp16 -> fp32 is exact, subnormals included).
+template <int R>
+__device__ __forceinline__ void reduce_grads(const f16x4 (&g)[R], float (&S)[4])
+{
+    S[0] = (float)g[0].x; S[1] = (float)g[0].y; S[2] = (float)g[0].z; S[3] = (float)g[0].w;
+#pragma unroll
+    for (int r = 1; r < R; ++r) {
+        S[0] += (float)g[r].x; S[1] += (float)g[r].y; S[2] += (float)g[r].z; S[3] += (float)g[r].w;
+    }
+}
+
+// The gradient source of a kernel: R fp16 slices reduced in registers, or (unfused pipelines) the fp32 sum
+// that a reduce kernel stored.
+template <int R>
+struct GradSlices {
+    gcbytes g[R];
+    struct Regs { f16x4 g[R]; };
+    __device__ __forceinline__ void init(const DevTensor *t, uint64_t base)
+    {
+#pragma unroll
+        for (int r = 0; r < R; ++r) g[r] = chunk_base((const void *)t->grad[r], base * 2);
+    }
+    __device__ __forceinline__ void load(Regs &x, uint32_t e) const
+    {
+#pragma unroll
+        for (int r = 0; r < R; ++r) x.g[r] = ld_f16x4(g[r], e * 2);
+    }
+    __device__ __forceinline__ void sum(const Regs &x, float (&S)[4]) const { reduce_grads<R>(x.g, S); }
+    __device__ __forceinline__ float sum1(uint32_t j) const
+    {
+        float S = ld_f16(g[0], j * 2);
+#pragma unroll
+        for (int r = 1; r < R; ++r) S += ld_f16(g[r], j * 2);
+        return S;
+    }
+};
+
+struct GradSum {
+    gcbytes s;
+    struct Regs { float s[4]; };
+    __device__ __forceinline__ void init(const DevTensor *t, uint64_t base) { s = chunk_base((const void *)t->gsum, base * 4); }
+    __device__ __forceinline__ void load(Regs &x, uint32_t e) const { ld_f32x4(s, e * 4, x.s); }
+    __device__ __forceinline__ void sum(const Regs &x, float (&S)[4]) const { S[0] = x.s[0]; S[1] = x.s[1]; S[2] = x.s[2]; S[3] = x.s[3]; }
+    __device__ __forceinline__ float sum1(uint32_t j) const { return ld_f32(s, j * 4); }
+};
+
+// ---------------------------------------------------------------------------------------------------
+// Adam: reduce (or read the reduced sum) + moments + weight update (+ fp16 emission when fused).
+// One pass, 2R + 26 bytes per parameter when fused.
+// ---------------------------------------------------------------------------------------------------
+template <class Grad, int MODE, bool EMIT16>
+struct AdamOp {
+    Grad grad;
+    gcbytes w_in, m_in, v_in;
+    gbytes w_out, m_out, v_out, w16;
+    StepScalars s;
+    float wd;
+    bool bad = false;
+    struct Regs { typename Grad::Regs g; float w[4], m[4], v[4]; };
+
+    __device__ __forceinline__ void init(const DevTensor *t, uint64_t base, const StepScalars &sc)
+    {
+        grad.init(t, base);
+        w_in = chunk_base((const void *)t->w_in, base * 4); m_in = chunk_base((const void *)t->m_in, base * 4);
+        v_in = chunk_base((const void *)t->v_in, base * 4);
+        w_out = chunk_base((void *)t->w_out, base * 4); m_out = chunk_base((void *)t->m_out, base * 4);
+        v_out = chunk_base((void *)t->v_out, base * 4);
+        w16 = chunk_base((void *)t->w16, base * 2);
+        s = sc;
+        wd = t->wd;
+    }
+    __device__ __forceinline__ void load(Regs &x, uint32_t e) const
+    {
+        grad.load(x.g, e);
+        ld_f32x4(w_in, e * 4, x.w); ld_f32x4(m_in, e * 4, x.m); ld_f32x4(v_in, e * 4, x.v);
+    }
+    __device__ __forceinline__ void one(float S, float &w, float &m, float &v)
+    {
+        const bool nf = not_finite(S);
+        bad |= nf;
+        float mk = m, vk = v;
+        moments<MODE>(S, w, wd, s, mk, vk);
+        const float wk = __builtin_fmaf(-s.lr, direction<MODE>(w, wd, mk, vk, s), w);
+        if (!(MODE & kModeGuard) || !nf) { m = mk; v = vk; w = wk; }
+    }
+    __device__ __forceinline__ void compute(Regs &x)
+    {
+        float S[4];
+        grad.sum(x.g, S);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) one(S[k], x.w[k], x.m[k], x.v[k]);
+    }
+    __device__ __forceinline__ void store(const Regs &x, uint32_t e) const
+    {
+        st_f32x4(m_out, e * 4, x.m); st_f32x4(v_out, e * 4, x.v); st_f32x4(w_out, e * 4, x.w);
+        if (EMIT16) st_f16x4(w16, e * 2, x.w);
+    }
+    __device__ __forceinline__ void single(uint32_t j)
+    {
+        float w = ld_f32(w_in, j * 4), m = ld_f32(m_in, j * 4), v = ld_f32(v_in, j * 4);
+        one(grad.sum1(j), w, m, v);
+        st_f32(m_out, j * 4, m); st_f32(v_out, j * 4, v); st_f32(w_out, j * 4, w);
+        if (EMIT16) st_f16(w16, j * 2, w);
+    }
+};
+
+template <int R, int MODE, int BLOCK>
+__global__ __launch_bounds__(BLOCK) void fused_adam_kernel(const DevTensor *__restrict__ tensors,
+                                                           const Chunk *__restrict__ chunks, StepScalars s,
+                                                           int32_t *__restrict__ flag)
+{
+    const Where wh = locate(tensors, chunks, s.chunk_elems);
+    AdamOp<GradSlices<R>, MODE, true> op;
+    op.init(wh.t, wh.base, s);
+    stream_chunk<BLOCK>(op, wh.len);
+    raise_flag(op.bad, flag);
+}
+
+// Unfused pipeline, optimizer stage: the same update from the stored fp32 sum; the cast kernel emits fp16.
+// In whole-step-skip mode the flag is already final here (the reduce kernel set it), so an overflowed step
+// writes nothing.
+template <int MODE, int BLOCK>
+__global__ __launch_bounds__(BLOCK) void adam_from_sum_kernel(const DevTensor *__restrict__ tensors,
+                                                              const Chunk *__restrict__ chunks, StepScalars s,
+                                                              const int32_t *__restrict__ flag)
+{
+    if (!(MODE & kModeGuard) && *flag != 0) return;
+    const Where wh = locate(tensors, chunks, s.chunk_elems);
+    AdamOp<GradSum, MODE, false> op;
+    op.init(wh.t, wh.base, s);
+    stream_chunk<BLOCK>(op, wh.len);
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Block-wide sum of two doubles: wave butterfly, then LDS across the 4 waves.  Same order every run.
+// Block-wide sum of two doubles: wave butterfly, then LDS across the waves.  Same order every run.
 // ---------------------------------------------------------------------------------------------------
 __device__ __forceinline__ double wave_sum(double x)
 {
@@ -263,105 +336,127 @@ __device__ __forceinline__ double wave_sum(double x)
     return x;
 }
 
+template <int BLOCK>
 __device__ __forceinline__ void block_sum2(double &a, double &b)
 {
-    __shared__ double lds[2][kBlock / 64];
+    constexpr int kWaves = BLOCK / 64;
     a = wave_sum(a);
     b = wave_sum(b);
-    const int wave = threadIdx.x >> 6;
-    if ((threadIdx.x & 63) == 0) { lds[0][wave] = a; lds[1][wave] = b; }
-    __syncthreads();
-    a = lds[0][0] + lds[0][1] + lds[0][2] + lds[0][3];
-    b = lds[1][0] + lds[1][1] + lds[1][2] + lds[1][3];
+    if (kWaves > 1) {
+        __shared__ double lds[2][kWaves];
+        const int wave = threadIdx.x >> 6;
+        if ((threadIdx.x & 63) == 0) { lds[0][wave] = a; lds[1][wave] = b; }
+        __syncthreads();
+        a = lds[0][0];
+        b = lds[1][0];
+#pragma unroll
+        for (int k = 1; k < kWaves; ++k) { a += lds[0][k]; b += lds[1][k]; }
+    }
 }
 
 // ---------------------------------------------------------------------------------------------------
 // LAMB phase 1: reduce, moments (written), and this chunk's sum(w^2), sum(u^2).
-// FROM_SUM: the reduced gradient is read from the fp32 buffer of the unfused pipeline instead.
 // ---------------------------------------------------------------------------------------------------
-template <int R, bool FROM_SUM>
-__global__ __launch_bounds__(kBlock) void lamb_phase1_kernel(const DevTensor *__restrict__ tensors,
-                                                             const Chunk *__restrict__ chunks, StepScalars s,
-                                                             double *__restrict__ partials,
-                                                             int32_t *__restrict__ flag)
+template <class Grad>
+struct LambPhase1Op {
+    Grad grad;
+    gcbytes w_in, m_in, v_in;
+    gbytes m_out, v_out;
+    StepScalars s;
+    float wd;
+    bool bad = false;
+    float sw = 0.f, su = 0.f;        // per lane: at most chunk_elems / BLOCK terms each, then double
+    struct Regs { typename Grad::Regs g; float w[4], m[4], v[4]; };
+
+    __device__ __forceinline__ void init(const DevTensor *t, uint64_t base, const StepScalars &sc)
+    {
+        grad.init(t, base);
+        w_in = chunk_base((const void *)t->w_in, base * 4); m_in = chunk_base((const void *)t->m_in, base * 4);
+        v_in = chunk_base((const void *)t->v_in, base * 4);
+        m_out = chunk_base((void *)t->m_out, base * 4); v_out = chunk_base((void *)t->v_out, base * 4);
+        s = sc;
+        wd = t->wd;
+    }
+    __device__ __forceinline__ void load(Regs &x, uint32_t e) const
+    {
+        grad.load(x.g, e);
+        ld_f32x4(w_in, e * 4, x.w); ld_f32x4(m_in, e * 4, x.m); ld_f32x4(v_in, e * 4, x.v);
+    }
+    __device__ __forceinline__ void one(float S, float w, float &m, float &v)
+    {
+        bad |= not_finite(S);
+        moments<0>(S, w, wd, s, m, v);
+        const float u = direction<0>(w, wd, m, v, s);
+        sw = __builtin_fmaf(w, w, sw);
+        su = __builtin_fmaf(u, u, su);
+    }
+    __device__ __forceinline__ void compute(Regs &x)
+    {
+        float S[4];
+        grad.sum(x.g, S);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) one(S[k], x.w[k], x.m[k], x.v[k]);
+    }
+    __device__ __forceinline__ void store(const Regs &x, uint32_t e) const
+    {
+        st_f32x4(m_out, e * 4, x.m); st_f32x4(v_out, e * 4, x.v);
+    }
+    __device__ __forceinline__ void single(uint32_t j)
+    {
+        const float w = ld_f32(w_in, j * 4);
+        float m = ld_f32(m_in, j * 4), v = ld_f32(v_in, j * 4);
+        one(grad.sum1(j), w, m, v);
+        st_f32(m_out, j * 4, m); st_f32(v_out, j * 4, v);
+    }
+};
+
+template <class Grad, bool RAISE, int BLOCK>
+__device__ __forceinline__ void lamb_phase1_body(const DevTensor *__restrict__ tensors, const Chunk *__restrict__ chunks,
+                                                 const StepScalars &s, double *__restrict__ partials, int32_t *__restrict__ flag)
 {
     const Where wh = locate(tensors, chunks, s.chunk_elems);
-    const DevTensor *t = wh.t;
-    const float wd = t->wd;
-    gcu16 gp[R];
-#pragma unroll
-    for (int r = 0; r < R; ++r) gp[r] = FROM_SUM ? (gcu16)nullptr : as_global(t->grad[r]) + wh.base;
-    const gcf32 gsum = FROM_SUM ? as_global((const float *)t->gsum) + wh.base : (gcf32)nullptr;
-    const gcf32 w_in = as_global(t->w_in) + wh.base, m_in = as_global(t->m_in) + wh.base, v_in = as_global(t->v_in) + wh.base;
-    const gf32 m_out = as_global(t->m_out) + wh.base, v_out = as_global(t->v_out) + wh.base;
-
-    bool bad = false;
-    float sw = 0.f, su = 0.f;            // per lane: at most chunk_elems / 256 terms each, then double
-    for (uint32_t i = threadIdx.x * kPack; i < wh.len; i += kSweep) {
-        if (i + kPack <= wh.len) {
-            float S[kPack], w[kPack], m[kPack], v[kPack];
-            if (FROM_SUM) {
-                const f32x4 s0 = ld4(gsum + i), s1 = ld4(gsum + i + 4);
-                const f32x4 w0 = ld4(w_in + i), w1 = ld4(w_in + i + 4);
-                const f32x4 m0 = ld4(m_in + i), m1 = ld4(m_in + i + 4);
-                const f32x4 v0 = ld4(v_in + i), v1 = ld4(v_in + i + 4);
-                unpack(s0, s1, S); unpack(w0, w1, w); unpack(m0, m1, m); unpack(v0, v1, v);
-            } else {
-                f16x8 g[R];
-                load_grads<R>(gp, i, g);
-                const f32x4 w0 = ld4(w_in + i), w1 = ld4(w_in + i + 4);
-                const f32x4 m0 = ld4(m_in + i), m1 = ld4(m_in + i + 4);
-                const f32x4 v0 = ld4(v_in + i), v1 = ld4(v_in + i + 4);
-                reduce_grads<R>(g, S);
-                unpack(w0, w1, w); unpack(m0, m1, m); unpack(v0, v1, v);
-            }
-#pragma unroll
-            for (int k = 0; k < kPack; ++k) {
-                bad |= not_finite(S[k]);
-                moments<0>(S[k], w[k], wd, s, m[k], v[k]);
-                const float u = direction<0>(w[k], wd, m[k], v[k], s);
-                sw = __builtin_fmaf(w[k], w[k], sw);
-                su = __builtin_fmaf(u, u, su);
-            }
-            store8(m_out + i, m);
-            store8(v_out + i, v);
-        } else {
-            for (uint32_t j = i; j < wh.len; ++j) {
-                const float S = FROM_SUM ? gsum[j] : reduce_one<R>(gp, j);
-                bad |= not_finite(S);
-                const float w = w_in[j];
-                float m = m_in[j], v = v_in[j];
-                moments<0>(S, w, wd, s, m, v);
-                const float u = direction<0>(w, wd, m, v, s);
-                sw = __builtin_fmaf(w, w, sw);
-                su = __builtin_fmaf(u, u, su);
-                m_out[j] = m;
-                v_out[j] = v;
-            }
-        }
-    }
-    double dw = sw, du = su;
-    block_sum2(dw, du);
+    LambPhase1Op<Grad> op;
+    op.init(wh.t, wh.base, s);
+    stream_chunk<BLOCK>(op, wh.len);
+    double dw = op.sw, du = op.su;
+    block_sum2<BLOCK>(dw, du);
     if (threadIdx.x == 0) {
         partials[2 * (uint64_t)blockIdx.x] = dw;
         partials[2 * (uint64_t)blockIdx.x + 1] = du;
     }
-    if (!FROM_SUM) raise_flag(bad, flag);
+    if (RAISE) raise_flag(op.bad, flag);
+}
+
+template <int R, int BLOCK>
+__global__ __launch_bounds__(BLOCK) void lamb_phase1_kernel(const DevTensor *__restrict__ tensors,
+                                                            const Chunk *__restrict__ chunks, StepScalars s,
+                                                            double *__restrict__ partials, int32_t *__restrict__ flag)
+{
+    lamb_phase1_body<GradSlices<R>, true, BLOCK>(tensors, chunks, s, partials, flag);
+}
+
+template <int BLOCK>
+__global__ __launch_bounds__(BLOCK) void lamb_phase1_from_sum_kernel(const DevTensor *__restrict__ tensors,
+                                                                     const Chunk *__restrict__ chunks, StepScalars s,
+                                                                     double *__restrict__ partials, int32_t *__restrict__ flag)
+{
+    lamb_phase1_body<GradSum, false, BLOCK>(tensors, chunks, s, partials, flag);
 }
 
 // LAMB second level: one workgroup per tensor adds that tensor's chunk partials in a fixed order.
-__global__ __launch_bounds__(kBlock) void lamb_norms_kernel(const DevTensor *__restrict__ tensors,
-                                                            const double *__restrict__ partials,
-                                                            double *__restrict__ sums)
+constexpr int kNormBlock = 256;
+__global__ __launch_bounds__(kNormBlock) void lamb_norms_kernel(const DevTensor *__restrict__ tensors,
+                                                                const double *__restrict__ partials,
+                                                                double *__restrict__ sums)
 {
     const DevTensor *t = tensors + blockIdx.x;
     const uint32_t first = t->first_chunk, n = t->num_chunks;
     double a = 0.0, b = 0.0;
-    for (uint32_t c = threadIdx.x; c < n; c += kBlock) {
+    for (uint32_t c = threadIdx.x; c < n; c += kNormBlock) {
         a += partials[2 * (uint64_t)(first + c)];
         b += partials[2 * (uint64_t)(first + c) + 1];
     }
-    block_sum2(a, b);
+    block_sum2<kNormBlock>(a, b);
     if (threadIdx.x == 0) {
         sums[2 * (uint64_t)blockIdx.x] = a;
         sums[2 * (uint64_t)blockIdx.x + 1] = b;
@@ -371,164 +466,147 @@ __global__ __launch_bounds__(kBlock) void lamb_norms_kernel(const DevTensor *__r
 // LAMB phase 2: the same u from the stored moments, scaled by the tensor's ratio.  EMIT16 = false in the
 // unfused pipeline, where a separate cast kernel writes the fp16 copy.
 template <bool EMIT16>
-__global__ __launch_bounds__(kBlock) void lamb_phase2_kernel(const DevTensor *__restrict__ tensors,
-                                                             const Chunk *__restrict__ chunks, StepScalars s,
-                                                             const double *__restrict__ sums,
-                                                             const int32_t *__restrict__ flag)
+struct LambPhase2Op {
+    gcbytes w_in, m_new, v_new;
+    gbytes w_out, w16;
+    StepScalars s;
+    float wd, step;
+    struct Regs { float w[4], m[4], v[4]; };
+
+    __device__ __forceinline__ void init(const DevTensor *t, uint64_t base, const StepScalars &sc, float ratio)
+    {
+        w_in = chunk_base((const void *)t->w_in, base * 4);
+        m_new = chunk_base((const void *)t->m_out, base * 4); v_new = chunk_base((const void *)t->v_out, base * 4);
+        w_out = chunk_base((void *)t->w_out, base * 4); w16 = chunk_base((void *)t->w16, base * 2);
+        s = sc;
+        wd = t->wd;
+        step = sc.lr * ratio;
+    }
+    __device__ __forceinline__ void load(Regs &x, uint32_t e) const
+    {
+        ld_f32x4(w_in, e * 4, x.w); ld_f32x4(m_new, e * 4, x.m); ld_f32x4(v_new, e * 4, x.v);
+    }
+    __device__ __forceinline__ float one(float w, float m, float v) const
+    {
+        return __builtin_fmaf(-step, direction<0>(w, wd, m, v, s), w);
+    }
+    __device__ __forceinline__ void compute(Regs &x)
+    {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) x.w[k] = one(x.w[k], x.m[k], x.v[k]);
+    }
+    __device__ __forceinline__ void store(const Regs &x, uint32_t e) const
+    {
+        st_f32x4(w_out, e * 4, x.w);
+        if (EMIT16) st_f16x4(w16, e * 2, x.w);
+    }
+    __device__ __forceinline__ void single(uint32_t j)
+    {
+        const float wn = one(ld_f32(w_in, j * 4), ld_f32(m_new, j * 4), ld_f32(v_new, j * 4));
+        st_f32(w_out, j * 4, wn);
+        if (EMIT16) st_f16(w16, j * 2, wn);
+    }
+};
+
+template <bool EMIT16, int BLOCK>
+__global__ __launch_bounds__(BLOCK) void lamb_phase2_kernel(const DevTensor *__restrict__ tensors,
+                                                            const Chunk *__restrict__ chunks, StepScalars s,
+                                                            const double *__restrict__ sums,
+                                                            const int32_t *__restrict__ flag)
 {
     if (*flag != 0) return;              // whole-step skip: w and w16 stay as they were
     const Where wh = locate(tensors, chunks, s.chunk_elems);
-    const DevTensor *t = wh.t;
-    const float wd = t->wd;
     const double sw = sums[2 * (uint64_t)wh.tensor], su = sums[2 * (uint64_t)wh.tensor + 1];
     const float ratio = (sw > 0.0 && su > 0.0) ? (float)(__builtin_sqrt(sw) / __builtin_sqrt(su)) : 1.0f;
-    const float step = s.lr * ratio;
-    const gcf32 w_in = as_global(t->w_in) + wh.base;
-    const gcf32 m_new = as_global((const float *)t->m_out) + wh.base, v_new = as_global((const float *)t->v_out) + wh.base;
-    const gf32 w_out = as_global(t->w_out) + wh.base;
-    const gu16 w16 = as_global(t->w16) + wh.base;
-    for (uint32_t i = threadIdx.x * kPack; i < wh.len; i += kSweep) {
-        if (i + kPack <= wh.len) {
-            const f32x4 w0 = ld4(w_in + i), w1 = ld4(w_in + i + 4);
-            const f32x4 m0 = ld4(m_new + i), m1 = ld4(m_new + i + 4);
-            const f32x4 v0 = ld4(v_new + i), v1 = ld4(v_new + i + 4);
-            float w[kPack], m[kPack], v[kPack];
-            unpack(w0, w1, w); unpack(m0, m1, m); unpack(v0, v1, v);
-#pragma unroll
-            for (int k = 0; k < kPack; ++k) w[k] = __builtin_fmaf(-step, direction<0>(w[k], wd, m[k], v[k], s), w[k]);
-            store8(w_out + i, w);
-            if (EMIT16) store8h(w16 + i, w);
-        } else {
-            for (uint32_t j = i; j < wh.len; ++j) {
-                const float w = w_in[j];
-                const float wn = __builtin_fmaf(-step, direction<0>(w, wd, m_new[j], v_new[j], s), w);
-                w_out[j] = wn;
-                if (EMIT16) sth(w16 + j, wn);
-            }
-        }
-    }
+    LambPhase2Op<EMIT16> op;
+    op.init(wh.t, wh.base, s, ratio);
+    stream_chunk<BLOCK>(op, wh.len);
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Unfused pipeline pieces: reduce to an fp32 buffer, optimizer on that buffer, cast.
+// Unfused pipeline pieces: reduce to an fp32 buffer, and the fp32 -> fp16 cast.
 // ---------------------------------------------------------------------------------------------------
 template <int R>
-__global__ __launch_bounds__(kBlock) void reduce_kernel(const DevTensor *__restrict__ tensors,
-                                                        const Chunk *__restrict__ chunks, StepScalars s,
-                                                        int32_t *__restrict__ flag)
+struct ReduceOp {
+    GradSlices<R> grad;
+    gbytes gsum;
+    bool bad = false;
+    struct Regs { typename GradSlices<R>::Regs g; float S[4]; };
+    __device__ __forceinline__ void init(const DevTensor *t, uint64_t base)
+    {
+        grad.init(t, base);
+        gsum = chunk_base((void *)t->gsum, base * 4);
+    }
+    __device__ __forceinline__ void load(Regs &x, uint32_t e) const { grad.load(x.g, e); }
+    __device__ __forceinline__ void compute(Regs &x)
+    {
+        grad.sum(x.g, x.S);
+        bad = bad || not_finite(x.S[0]) || not_finite(x.S[1]) || not_finite(x.S[2]) || not_finite(x.S[3]);
+    }
+    __device__ __forceinline__ void store(const Regs &x, uint32_t e) const { st_f32x4(gsum, e * 4, x.S); }
+    __device__ __forceinline__ void single(uint32_t j)
+    {
+        const float S = grad.sum1(j);
+        bad |= not_finite(S);
+        st_f32(gsum, j * 4, S);
+    }
+};
+
+template <int R, int BLOCK>
+__global__ __launch_bounds__(BLOCK) void reduce_kernel(const DevTensor *__restrict__ tensors,
+                                                       const Chunk *__restrict__ chunks, StepScalars s,
+                                                       int32_t *__restrict__ flag)
 {
     const Where wh = locate(tensors, chunks, s.chunk_elems);
-    const DevTensor *t = wh.t;
-    gcu16 gp[R];
-#pragma unroll
-    for (int r = 0; r < R; ++r) gp[r] = as_global(t->grad[r]) + wh.base;
-    const gf32 gsum = as_global(t->gsum) + wh.base;
-    bool bad = false;
-    for (uint32_t i = threadIdx.x * kPack; i < wh.len; i += kSweep) {
-        if (i + kPack <= wh.len) {
-            f16x8 g[R];
-            load_grads<R>(gp, i, g);
-            float S[kPack];
-            reduce_grads<R>(g, S);
-#pragma unroll
-            for (int k = 0; k < kPack; ++k) bad |= not_finite(S[k]);
-            store8(gsum + i, S);
-        } else {
-            for (uint32_t j = i; j < wh.len; ++j) {
-                const float S = reduce_one<R>(gp, j);
-                bad |= not_finite(S);
-                gsum[j] = S;
-            }
-        }
-    }
-    raise_flag(bad, flag);
+    ReduceOp<R> op;
+    op.init(wh.t, wh.base);
+    stream_chunk<BLOCK>(op, wh.len);
+    raise_flag(op.bad, flag);
 }
 
-template <int MODE>
-__global__ __launch_bounds__(kBlock) void adam_from_sum_kernel(const DevTensor *__restrict__ tensors,
-                                                               const Chunk *__restrict__ chunks, StepScalars s,
-                                                               const int32_t *__restrict__ flag)
-{
-    if (!(MODE & kModeGuard) && *flag != 0) return;
-    const Where wh = locate(tensors, chunks, s.chunk_elems);
-    const DevTensor *t = wh.t;
-    const float wd = t->wd;
-    const gcf32 gsum = as_global((const float *)t->gsum) + wh.base;
-    const gcf32 w_in = as_global(t->w_in) + wh.base, m_in = as_global(t->m_in) + wh.base, v_in = as_global(t->v_in) + wh.base;
-    const gf32 w_out = as_global(t->w_out) + wh.base, m_out = as_global(t->m_out) + wh.base, v_out = as_global(t->v_out) + wh.base;
-    for (uint32_t i = threadIdx.x * kPack; i < wh.len; i += kSweep) {
-        if (i + kPack <= wh.len) {
-            const f32x4 s0 = ld4(gsum + i), s1 = ld4(gsum + i + 4);
-            const f32x4 w0 = ld4(w_in + i), w1 = ld4(w_in + i + 4);
-            const f32x4 m0 = ld4(m_in + i), m1 = ld4(m_in + i + 4);
-            const f32x4 v0 = ld4(v_in + i), v1 = ld4(v_in + i + 4);
-            float S[kPack], w[kPack], m[kPack], v[kPack];
-            unpack(s0, s1, S); unpack(w0, w1, w); unpack(m0, m1, m); unpack(v0, v1, v);
-#pragma unroll
-            for (int k = 0; k < kPack; ++k) {
-                const bool nf = not_finite(S[k]);
-                float mk = m[k], vk = v[k];
-                moments<MODE>(S[k], w[k], wd, s, mk, vk);
-                const float wk = __builtin_fmaf(-s.lr, direction<MODE>(w[k], wd, mk, vk, s), w[k]);
-                if (!(MODE & kModeGuard) || !nf) { m[k] = mk; v[k] = vk; w[k] = wk; }
-            }
-            store8(m_out + i, m);
-            store8(v_out + i, v);
-            store8(w_out + i, w);
-        } else {
-            for (uint32_t j = i; j < wh.len; ++j) {
-                const float S = gsum[j];
-                const float w = w_in[j];
-                float m = m_in[j], v = v_in[j];
-                float wn = w;
-                if (!(MODE & kModeGuard) || !not_finite(S)) {
-                    moments<MODE>(S, w, wd, s, m, v);
-                    wn = __builtin_fmaf(-s.lr, direction<MODE>(w, wd, m, v, s), w);
-                }
-                m_out[j] = m;
-                v_out[j] = v;
-                w_out[j] = wn;
-            }
-        }
+struct CastOp {
+    gcbytes w_new;
+    gbytes w16;
+    struct Regs { float w[4]; };
+    __device__ __forceinline__ void init(const DevTensor *t, uint64_t base)
+    {
+        w_new = chunk_base((const void *)t->w_out, base * 4);
+        w16 = chunk_base((void *)t->w16, base * 2);
     }
-}
+    __device__ __forceinline__ void load(Regs &x, uint32_t e) const { ld_f32x4(w_new, e * 4, x.w); }
+    __device__ __forceinline__ void compute(Regs &) {}
+    __device__ __forceinline__ void store(const Regs &x, uint32_t e) const { st_f16x4(w16, e * 2, x.w); }
+    __device__ __forceinline__ void single(uint32_t j) { st_f16(w16, j * 2, ld_f32(w_new, j * 4)); }
+};
 
 // fp32 master weights -> fp16 copy.  `guarded`: leave w16 alone on overflow (whole-step skip).
-__global__ __launch_bounds__(kBlock) void cast_kernel(const DevTensor *__restrict__ tensors,
-                                                      const Chunk *__restrict__ chunks, StepScalars s,
-                                                      const int32_t *__restrict__ flag, int guarded)
+template <int BLOCK>
+__global__ __launch_bounds__(BLOCK) void cast_kernel(const DevTensor *__restrict__ tensors,
+                                                     const Chunk *__restrict__ chunks, StepScalars s,
+                                                     const int32_t *__restrict__ flag, int guarded)
 {
     if (guarded && *flag != 0) return;
     const Where wh = locate(tensors, chunks, s.chunk_elems);
-    const DevTensor *t = wh.t;
-    const gcf32 w_new = as_global((const float *)t->w_out) + wh.base;
-    const gu16 w16 = as_global(t->w16) + wh.base;
-    for (uint32_t i = threadIdx.x * kPack; i < wh.len; i += kSweep) {
-        if (i + kPack <= wh.len) {
-            const f32x4 w0 = ld4(w_new + i), w1 = ld4(w_new + i + 4);
-            float w[kPack];
-            unpack(w0, w1, w);
-            store8h(w16 + i, w);
-        } else {
-            for (uint32_t j = i; j < wh.len; ++j) sth(w16 + j, w_new[j]);
-        }
-    }
+    CastOp op;
+    op.init(wh.t, wh.base);
+    stream_chunk<BLOCK>(op, wh.len);
 }
 
 // Plain streaming copy, 16 bytes per lane, four accesses in flight per lane.
-__global__ __launch_bounds__(kBlock) void copy_kernel(u32x4 *__restrict__ dst, const u32x4 *__restrict__ src,
-                                                      uint64_t n16)
+constexpr int kCopyBlock = 256;
+__global__ __launch_bounds__(kCopyBlock) void copy_kernel(u32x4 *__restrict__ dst, const u32x4 *__restrict__ src,
+                                                          uint64_t n16)
 {
-    const uint64_t base = (uint64_t)blockIdx.x * (kBlock * 4) + threadIdx.x;
+    const uint64_t base = (uint64_t)blockIdx.x * (kCopyBlock * 4) + threadIdx.x;
     u32x4 x[4];
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
-        const uint64_t i = base + (uint64_t)k * kBlock;
+        const uint64_t i = base + (uint64_t)k * kCopyBlock;
         if (i < n16) x[k] = __builtin_nontemporal_load(src + i);
     }
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
-        const uint64_t i = base + (uint64_t)k * kBlock;
+        const uint64_t i = base + (uint64_t)k * kCopyBlock;
         if (i < n16) __builtin_nontemporal_store(x[k], dst + i);
     }
 }
