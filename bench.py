@@ -23,6 +23,10 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 
+# HBM bytes per launch of the headline kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by what
+# the same counter reads for the plain copy kernel (profiles/fused_adam_config2.md): default chunk size only.
+MEASURED_TRAFFIC_BYTES = {2: 9.4256e9 + 4.7069e9}
+
 
 def adam_bytes_per_param(R):   # read 2R (fp16 grads) + 12 (w, m, v); write 12 (w, m, v) + 2 (fp16 w)
     return 2 * R + 26
@@ -49,6 +53,7 @@ def main() -> int:
     ap.add_argument("--chunk-elems", type=int, default=0)
     ap.add_argument("--in-place", action="store_true", help="in-place state with the per-element guard (skip_mode 1)")
     ap.add_argument("--no-extras", action="store_true", help="only the headline step (for profiling runs)")
+    ap.add_argument("--copy-only", action="store_true", help="run only the plain copy kernel (2 GiB, 20 launches): counter calibration")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     args = ap.parse_args()
 
@@ -69,6 +74,15 @@ def main() -> int:
     cc.load()                                            # raises if libccfused.so is missing
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
+    if args.copy_only:
+        nbytes = 2 << 30
+        src = torch.empty(nbytes, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        for _ in range(20):
+            cc.cc_copy_probe(dst, src, nbytes)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_only": True, "bytes_read_per_launch": nbytes, "bytes_written_per_launch": nbytes, "launches": 20}))
+        return 0
     cfg = W.config(args.config)
     R, N = cfg.R, cfg.numel
     K, Wm = args.steps, args.warmup
@@ -130,7 +144,8 @@ def main() -> int:
                    "chunk_elems": args.chunk_elems or cc.cc_default_chunk_elems(), "chunks": chunks,
                    "table_bytes": table_bytes, "algorithmic_bytes_per_param": bpp},
         "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                     "frac": round(gbs / HBM_PEAK_GBS, 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.index) if (args.chunk_elems == 0 and not args.in_place) else None,
                      "kernel": "fused_adam_kernel<R=%d>" % R if cfg.optimizer == "adam" else "lamb_phase1_kernel + lamb_phase2_kernel",
                      "bytes_per_launch": bpp * N, "avg_launch_ms": round(ms, 5)},
     }

@@ -18,7 +18,7 @@ namespace {
 
 constexpr int32_t kDefaultChunkElems = 4096;
 constexpr int32_t kMaxChunkElems = 1 << 24;     // lane offsets inside a chunk are 32-bit byte offsets
-constexpr int kBlock = 256;                      // threads per workgroup of the streaming kernels
+constexpr int kBlock = 512;                      // threads per workgroup: one sweep of 2 groups x 512 x 4 = the default chunk
 
 thread_local char g_err[512] = "";
 

@@ -164,22 +164,23 @@ __global__ void clear_flag_kernel(int32_t *flag) { *flag = 0; }
 //   void single(uint32_t j);                       one element, scalar accesses (ragged end of a tensor)
 // A sweep is two groups BLOCK*4 elements apart.  A full sweep issues the loads of both groups, then computes
 // and stores; the ragged end of a chunk (only a tensor's last chunk has one) falls back group by group.
-template <int BLOCK, class Op>
+template <int BLOCK, class Op, int GROUPS = 2>
 __device__ __forceinline__ void stream_chunk(Op &op, uint32_t len)
 {
     constexpr uint32_t kGroup = BLOCK * kLanePack;
-    constexpr uint32_t kSweep = 2 * kGroup;
+    constexpr uint32_t kSweep = GROUPS * kGroup;
     const uint32_t lane_e = threadIdx.x * kLanePack;
     uint32_t s0 = 0;
     for (; s0 + kSweep <= len; s0 += kSweep) {
-        typename Op::Regs a, b;
-        op.load(a, s0 + lane_e);
-        op.load(b, s0 + kGroup + lane_e);
+        typename Op::Regs x[GROUPS];
+#pragma unroll
+        for (int g = 0; g < GROUPS; ++g) op.load(x[g], s0 + g * kGroup + lane_e);
         __builtin_amdgcn_sched_barrier(0);         // keep all loads of the sweep ahead of the first use
-        op.compute(a);
-        op.store(a, s0 + lane_e);
-        op.compute(b);
-        op.store(b, s0 + kGroup + lane_e);
+#pragma unroll
+        for (int g = 0; g < GROUPS; ++g) {
+            op.compute(x[g]);
+            op.store(x[g], s0 + g * kGroup + lane_e);
+        }
     }
     for (uint32_t e = s0 + lane_e; e < len; e += kGroup) {
         if (e + kLanePack <= len) {
@@ -299,7 +300,7 @@ struct AdamOp {
     }
 };
 
-template <int R, int MODE, int BLOCK>
+template <int R, int MODE, int BLOCK, int GROUPS = 2>
 __global__ __launch_bounds__(BLOCK) void fused_adam_kernel(const DevTensor *__restrict__ tensors,
                                                            const Chunk *__restrict__ chunks, StepScalars s,
                                                            int32_t *__restrict__ flag)
@@ -307,7 +308,7 @@ __global__ __launch_bounds__(BLOCK) void fused_adam_kernel(const DevTensor *__re
     const Where wh = locate(tensors, chunks, s.chunk_elems);
     AdamOp<GradSlices<R>, MODE, true> op;
     op.init(wh.t, wh.base, s);
-    stream_chunk<BLOCK>(op, wh.len);
+    stream_chunk<BLOCK, decltype(op), GROUPS>(op, wh.len);
     raise_flag(op.bad, flag);
 }
 
