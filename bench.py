@@ -52,6 +52,7 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=2, help="workload configuration 1..5 (default 2, the metric's)")
     ap.add_argument("--chunk-elems", type=int, default=0)
     ap.add_argument("--in-place", action="store_true", help="in-place state with the per-element guard (skip_mode 1)")
+    ap.add_argument("--graph", action="store_true", help="enqueue the timed steps as replays of a captured HIP graph of 20 steps")
     ap.add_argument("--no-extras", action="store_true", help="only the headline step (for profiling runs)")
     ap.add_argument("--copy-only", action="store_true", help="run only the plain copy kernel (2 GiB, 20 launches): counter calibration")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
@@ -109,6 +110,24 @@ def main() -> int:
             t += 1
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        if args.graph:
+            # launch-bound sizes: the same calls, recorded once (an even number of steps, so that the ping-pong
+            # state is back where it started) and replayed; the step count t is baked into the recording
+            per = 20
+            assert steps % per == 0, "--graph needs --steps to be a multiple of 20"
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                for i in range(per):
+                    shard.run(step_fn, hyper(t + i))
+                    shard.commit()
+            g.replay()
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(steps // per):
+                g.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / steps, int(shard.flag.item()), t + per
         e0.record()
         for _ in range(steps):
             shard.run(step_fn, hyper(t))
@@ -141,7 +160,8 @@ def main() -> int:
                                              {1: "one flat tensor", 2: "BERT-Large parameter list", 3: "BERT-Large parameter list",
                                               4: "GPT-2 1.5B parameter list", 5: "1/8 shard of an 8.3B transformer"}[cfg.index],
                                              len(cfg.params), N, R, "in-place" if args.in_place else "out-of-place (ping-pong)"),
-                   "chunk_elems": args.chunk_elems or cc.cc_default_chunk_elems(), "chunks": chunks,
+                   "chunk_elems": (N + chunks - 1) // chunks if cfg.index == 1 and chunks else (args.chunk_elems or cc.cc_default_chunk_elems()),
+                   "chunks": chunks, "launch": "hip graph replay" if args.graph else "eager",
                    "table_bytes": table_bytes, "algorithmic_bytes_per_param": bpp},
         "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(gbs / HBM_PEAK_GBS, 4),

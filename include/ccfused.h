@@ -98,7 +98,8 @@ int64_t cc_chunk_count(const uint64_t *numels, int32_t T, int32_t chunk_elems);
 int64_t cc_chunk_table_fill(const uint64_t *numels, int32_t T, int32_t chunk_elems,
                             uint32_t *table, int64_t capacity);
 
-/* Default chunk size in elements (a tuning choice of this library; the paper's buckets hold 2^10). */
+/* Default chunk size in elements for large shards (a tuning choice of this library; the paper's buckets hold
+ * 2^10).  Shards below 4 Mi elements default to 1024-element chunks, for more workgroups. */
 int32_t cc_default_chunk_elems(void);
 
 /* ---- plan ---- */
@@ -106,7 +107,8 @@ int32_t cc_default_chunk_elems(void);
 /*
  * Validates the T tensors (host array, copied) and builds the device-side descriptor array and chunk
  * table once, like the paper's wrapper pre-computes bucket pointers (Section 5.5).  R = number of
- * gradient slices per tensor, 1..CC_MAX_R.  chunk_elems: 0 = default, else a positive multiple of 1024.
+ * gradient slices per tensor, 1..CC_MAX_R.  chunk_elems: 0 = default, else a positive multiple of 1024 up to 2^24
+ * (chunks of 4096 and more run in 512-thread workgroups, smaller ones in 128-thread workgroups).
  * The plan owns only its own tables and scratch; it keeps raw copies of the caller's pointers, which
  * must stay valid while the plan is used.  Tensors with numel == 0 are legal and produce no chunks.
  */
@@ -123,7 +125,8 @@ int cc_plan_info(const cc_plan *plan, uint64_t *numel, int64_t *chunks, uint64_t
  *   S = g_0[i] + g_1[i] + ... + g_{R-1}[i]   (fixed rank order)     gh = S / (loss_scale * (avg ? R : 1))
  *   m' = beta1 m + (1-beta1) gh      v' = beta2 v + (1-beta2) gh^2
  *   u  = (m'/(1-beta1^t)) / (sqrt(v'/(1-beta2^t)) + eps) + wd w     w' = w - lr u     w16 = fp16(w')
- * *d_overflow_flag (device int32) is cleared by the call and set to 1 if any S is inf or NaN.
+ * *d_overflow_flag (device int32) is written by the call: 1 if any S is inf or NaN, else 0 (the same launch that
+ * does the update writes it; there is no separate clearing launch).
  * skip_mode 0: outputs are written unconditionally to the (distinct) out buffers; they are valid only
  * if the flag reads 0 afterwards.  skip_mode 1: see cc_hparams.
  */

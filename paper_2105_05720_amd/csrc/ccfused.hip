@@ -16,9 +16,11 @@ using namespace ccf;
 
 namespace {
 
-constexpr int32_t kDefaultChunkElems = 4096;
-constexpr int32_t kMaxChunkElems = 1 << 24;     // lane offsets inside a chunk are 32-bit byte offsets
-constexpr int kBlock = 512;                      // threads per workgroup: one sweep of 2 groups x 512 x 4 = the default chunk
+constexpr int32_t kDefaultChunkElems = 4096;     // one sweep of a 512-thread workgroup (2 groups x 512 lanes x 4 elements)
+constexpr int32_t kSmallChunkElems = 1024;       // one sweep of a 128-thread workgroup: more workgroups for small shards
+constexpr uint64_t kSmallShardElems = 4u << 20;  // below this many elements the default chunk is the small one
+constexpr int32_t kMaxChunkElems = 1 << 24;      // lane offsets inside a chunk are 32-bit byte offsets
+constexpr int kBigBlock = 512, kSmallBlock = 128;
 
 thread_local char g_err[512] = "";
 
@@ -37,9 +39,9 @@ int fail(cc_status code, const char *fmt, ...)
         if (e_ != hipSuccess) return fail(CC_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_));     \
     } while (0)
 
-int32_t resolve_chunk(int32_t chunk_elems)
+int32_t resolve_chunk(int32_t chunk_elems, uint64_t total_elems = ~0ull)
 {
-    if (chunk_elems == 0) return kDefaultChunkElems;
+    if (chunk_elems == 0) return total_elems < kSmallShardElems ? kSmallChunkElems : kDefaultChunkElems;
     if (chunk_elems < 0 || chunk_elems % 1024 != 0 || chunk_elems > kMaxChunkElems) return -1;
     return chunk_elems;
 }
@@ -59,6 +61,8 @@ int overlap(const void *a, const void *b, uint64_t bytes)
 
 struct cc_plan {
     int32_t T = 0, R = 0, chunk_elems = 0;
+    int block = kBigBlock;                  // threads per workgroup of the streaming kernels
+    FlagScratch *d_flag_scratch = nullptr;  // {done, bad}, zero between launches
     int64_t chunks = 0;
     uint64_t numel = 0;
     bool in_place = false;                  // some tensor has out == in
@@ -119,8 +123,10 @@ int cc_plan_create(const cc_tensor *tensors, int32_t T, int32_t R, int32_t chunk
     if (!tensors) return fail(CC_ERR_NULL, "cc_plan_create: tensors is NULL");
     if (T <= 0) return fail(CC_ERR_ARG, "cc_plan_create: T = %d must be positive", T);
     if (R < 1 || R > CC_MAX_R) return fail(CC_ERR_ARG, "cc_plan_create: R = %d outside 1..%d", R, CC_MAX_R);
-    const int32_t ce = resolve_chunk(chunk_elems);
-    if (ce < 0) return fail(CC_ERR_ARG, "chunk_elems = %d is not a positive multiple of 1024 up to 2^24", chunk_elems);
+    if (resolve_chunk(chunk_elems) < 0) return fail(CC_ERR_ARG, "chunk_elems = %d is not a positive multiple of 1024 up to 2^24", chunk_elems);
+    uint64_t total_elems = 0;
+    for (int32_t t = 0; t < T; ++t) total_elems += tensors[t].numel;
+    const int32_t ce = resolve_chunk(chunk_elems, total_elems);
 
     bool in_place = false;
     std::vector<uint64_t> numels((size_t)T);
@@ -150,6 +156,7 @@ int cc_plan_create(const cc_tensor *tensors, int32_t T, int32_t R, int32_t chunk
     cc_plan *p = new (std::nothrow) cc_plan;
     if (!p) return fail(CC_ERR_NOMEM, "cc_plan_create: out of host memory");
     p->T = T; p->R = R; p->chunk_elems = ce; p->chunks = chunks; p->in_place = in_place;
+    p->block = ce >= kDefaultChunkElems ? kBigBlock : kSmallBlock;
     std::vector<uint32_t> table;
     try {
         p->host_tensors.resize((size_t)T);
@@ -197,6 +204,8 @@ int cc_plan_create(const cc_tensor *tensors, int32_t T, int32_t R, int32_t chunk
     PLAN_TRY(hipMalloc((void **)&p->d_partials, sizeof(double) * 2 * (size_t)(chunks + 1)));
     PLAN_TRY(hipMalloc((void **)&p->d_sums, sizeof(double) * 2 * (size_t)T));
     PLAN_TRY(hipMemset(p->d_sums, 0, sizeof(double) * 2 * (size_t)T));
+    PLAN_TRY(hipMalloc((void **)&p->d_flag_scratch, sizeof(FlagScratch)));
+    PLAN_TRY(hipMemset(p->d_flag_scratch, 0, sizeof(FlagScratch)));
 #undef PLAN_TRY
     *out = p;
     return CC_OK;
@@ -210,6 +219,7 @@ int cc_plan_destroy(cc_plan *p)
     if (p->d_partials) (void)hipFree(p->d_partials);
     if (p->d_sums) (void)hipFree(p->d_sums);
     if (p->d_gsum) (void)hipFree(p->d_gsum);
+    if (p->d_flag_scratch) (void)hipFree(p->d_flag_scratch);
     delete p;
     return CC_OK;
 }
@@ -296,40 +306,73 @@ int ensure_gsum(cc_plan *p)
 
 #define FOR_EACH_R(X) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13) X(14) X(15) X(16)
 
-template <int MODE>
+// Every streaming kernel exists for two workgroup sizes; the plan picks one from its chunk size.
+#define BY_BLOCK(p, CALL)                      \
+    do {                                       \
+        if ((p)->block == kBigBlock) { constexpr int BLK = kBigBlock; CALL; } \
+        else { constexpr int BLK = kSmallBlock; CALL; }                       \
+    } while (0)
+
+template <int MODE, int BLK>
 void launch_fused_adam(const cc_plan *p, const StepScalars &s, int32_t *flag, hipStream_t st)
 {
-    const dim3 grid((unsigned)p->chunks), block(kBlock);
+    const dim3 grid((unsigned)p->chunks), block(BLK);
     switch (p->R) {
-#define CASE(r) case r: hipLaunchKernelGGL((fused_adam_kernel<r, MODE, kBlock>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag); break;
+#define CASE(r) case r: hipLaunchKernelGGL((fused_adam_kernel<r, MODE, BLK>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, p->d_flag_scratch, flag); break;
         FOR_EACH_R(CASE)
 #undef CASE
     }
 }
 
+template <int BLK>
 void launch_lamb_phase1(const cc_plan *p, const StepScalars &s, int32_t *flag, hipStream_t st)
 {
-    const dim3 grid((unsigned)p->chunks), block(kBlock);
+    const dim3 grid((unsigned)p->chunks), block(BLK);
     switch (p->R) {
-#define CASE(r) case r: hipLaunchKernelGGL((lamb_phase1_kernel<r, kBlock>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, p->d_partials, flag); break;
+#define CASE(r) case r: hipLaunchKernelGGL((lamb_phase1_kernel<r, BLK>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, p->d_partials, p->d_flag_scratch, flag); break;
         FOR_EACH_R(CASE)
 #undef CASE
     }
 }
 
+template <int BLK>
 void launch_reduce(const cc_plan *p, const StepScalars &s, int32_t *flag, hipStream_t st)
 {
-    const dim3 grid((unsigned)p->chunks), block(kBlock);
+    const dim3 grid((unsigned)p->chunks), block(BLK);
     switch (p->R) {
-#define CASE(r) case r: hipLaunchKernelGGL((reduce_kernel<r, kBlock>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag); break;
+#define CASE(r) case r: hipLaunchKernelGGL((reduce_kernel<r, BLK>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, p->d_flag_scratch, flag); break;
         FOR_EACH_R(CASE)
 #undef CASE
     }
 }
 
+template <int BLK>
+void launch_adam_from_sum(const cc_plan *p, const StepScalars &s, const int32_t *flag, hipStream_t st, int mode)
+{
+    const dim3 grid((unsigned)p->chunks), block(BLK);
+    switch (mode) {
+        case 0: hipLaunchKernelGGL((adam_from_sum_kernel<0, BLK>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag); break;
+        case 1: hipLaunchKernelGGL((adam_from_sum_kernel<1, BLK>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag); break;
+        case 2: hipLaunchKernelGGL((adam_from_sum_kernel<2, BLK>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag); break;
+        default: hipLaunchKernelGGL((adam_from_sum_kernel<3, BLK>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag); break;
+    }
+}
+
+template <int BLK>
+void launch_fused_adam_mode(const cc_plan *p, const StepScalars &s, int32_t *flag, hipStream_t st, int mode)
+{
+    switch (mode) {
+        case 0: launch_fused_adam<0, BLK>(p, s, flag, st); break;
+        case 1: launch_fused_adam<1, BLK>(p, s, flag, st); break;
+        case 2: launch_fused_adam<2, BLK>(p, s, flag, st); break;
+        default: launch_fused_adam<3, BLK>(p, s, flag, st); break;
+    }
+}
+
+// A plan without chunks launches no streaming kernel, so the flag is cleared by a one-thread kernel (a kernel
+// rather than a memset node, so that the call can still be captured into a HIP graph).
 int clear_flag(int32_t *flag, hipStream_t st)
 {
-    // a one-thread kernel rather than a memset node, so that the call can be captured into a HIP graph
     hipLaunchKernelGGL(clear_flag_kernel, dim3(1), dim3(1), 0, st, flag);
     return launched("clear_flag_kernel");
 }
@@ -337,9 +380,9 @@ int clear_flag(int32_t *flag, hipStream_t st)
 int lamb_phase2_impl(cc_plan *p, const StepScalars &s, const int32_t *flag, hipStream_t st, bool emit16)
 {
     if (p->chunks == 0) return CC_OK;
-    const dim3 grid((unsigned)p->chunks), block(kBlock);
-    if (emit16) hipLaunchKernelGGL((lamb_phase2_kernel<true, kBlock>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, p->d_sums, flag);
-    else hipLaunchKernelGGL((lamb_phase2_kernel<false, kBlock>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, p->d_sums, flag);
+    const dim3 grid((unsigned)p->chunks);
+    if (emit16) BY_BLOCK(p, hipLaunchKernelGGL((lamb_phase2_kernel<true, BLK>), grid, dim3(BLK), 0, st, p->d_tensors, p->d_chunks, s, p->d_sums, flag));
+    else BY_BLOCK(p, hipLaunchKernelGGL((lamb_phase2_kernel<false, BLK>), grid, dim3(BLK), 0, st, p->d_tensors, p->d_chunks, s, p->d_sums, flag));
     return launched("lamb_phase2_kernel");
 }
 
@@ -347,6 +390,13 @@ int lamb_norms(cc_plan *p, hipStream_t st)
 {
     hipLaunchKernelGGL(lamb_norms_kernel, dim3((unsigned)p->T), dim3(kNormBlock), 0, st, p->d_tensors, p->d_partials, p->d_sums);
     return launched("lamb_norms_kernel");
+}
+
+int cast_launch(cc_plan *p, const StepScalars &s, const int32_t *flag, hipStream_t st, int guarded)
+{
+    const dim3 grid((unsigned)p->chunks);
+    BY_BLOCK(p, hipLaunchKernelGGL((cast_kernel<BLK>), grid, dim3(BLK), 0, st, p->d_tensors, p->d_chunks, s, flag, guarded));
+    return launched("cast_kernel");
 }
 
 }  // namespace
@@ -359,15 +409,9 @@ int cc_fused_adam_step(cc_plan *p, const cc_hparams *hp, int32_t *flag, void *st
     int rc = check_step(p, hp, flag, Opt::Adam, &s);
     if (rc) return rc;
     hipStream_t st = (hipStream_t)stream;
-    if ((rc = clear_flag(flag, st))) return rc;
-    if (p->chunks == 0) return CC_OK;
+    if (p->chunks == 0) return clear_flag(flag, st);
     const int mode = (hp->skip_mode == 1 ? kModeGuard : 0) | (hp->adam_mode == 0 ? kModeL2 : 0);
-    switch (mode) {
-        case 0: launch_fused_adam<0>(p, s, flag, st); break;
-        case 1: launch_fused_adam<1>(p, s, flag, st); break;
-        case 2: launch_fused_adam<2>(p, s, flag, st); break;
-        default: launch_fused_adam<3>(p, s, flag, st); break;
-    }
+    BY_BLOCK(p, launch_fused_adam_mode<BLK>(p, s, flag, st, mode));
     return launched("fused_adam_kernel");
 }
 
@@ -377,9 +421,10 @@ int cc_fused_lamb_phase1(cc_plan *p, const cc_hparams *hp, int32_t *flag, void *
     int rc = check_step(p, hp, flag, Opt::Lamb, &s);
     if (rc) return rc;
     hipStream_t st = (hipStream_t)stream;
-    if ((rc = clear_flag(flag, st))) return rc;
-    if (p->chunks > 0) {
-        launch_lamb_phase1(p, s, flag, st);
+    if (p->chunks == 0) {
+        if ((rc = clear_flag(flag, st))) return rc;
+    } else {
+        BY_BLOCK(p, launch_lamb_phase1<BLK>(p, s, flag, st));
         if ((rc = launched("lamb_phase1_kernel"))) return rc;
     }
     return lamb_norms(p, st);
@@ -407,21 +452,13 @@ int cc_unfused_adam_step(cc_plan *p, const cc_hparams *hp, int32_t *flag, void *
     if (rc) return rc;
     if ((rc = ensure_gsum(p))) return rc;
     hipStream_t st = (hipStream_t)stream;
-    if ((rc = clear_flag(flag, st))) return rc;
-    if (p->chunks == 0) return CC_OK;
-    const dim3 grid((unsigned)p->chunks), block(kBlock);
-    launch_reduce(p, s, flag, st);
+    if (p->chunks == 0) return clear_flag(flag, st);
+    BY_BLOCK(p, launch_reduce<BLK>(p, s, flag, st));
     if ((rc = launched("reduce_kernel"))) return rc;
     const int mode = (hp->skip_mode == 1 ? kModeGuard : 0) | (hp->adam_mode == 0 ? kModeL2 : 0);
-    switch (mode) {
-        case 0: hipLaunchKernelGGL((adam_from_sum_kernel<0, kBlock>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag); break;
-        case 1: hipLaunchKernelGGL((adam_from_sum_kernel<1, kBlock>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag); break;
-        case 2: hipLaunchKernelGGL((adam_from_sum_kernel<2, kBlock>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag); break;
-        default: hipLaunchKernelGGL((adam_from_sum_kernel<3, kBlock>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag); break;
-    }
+    BY_BLOCK(p, launch_adam_from_sum<BLK>(p, s, flag, st, mode));
     if ((rc = launched("adam_from_sum_kernel"))) return rc;
-    hipLaunchKernelGGL((cast_kernel<kBlock>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag, hp->skip_mode == 0 ? 1 : 0);
-    return launched("cast_kernel");
+    return cast_launch(p, s, flag, st, hp->skip_mode == 0 ? 1 : 0);
 }
 
 int cc_unfused_lamb_step(cc_plan *p, const cc_hparams *hp, int32_t *flag, void *stream)
@@ -431,22 +468,18 @@ int cc_unfused_lamb_step(cc_plan *p, const cc_hparams *hp, int32_t *flag, void *
     if (rc) return rc;
     if ((rc = ensure_gsum(p))) return rc;
     hipStream_t st = (hipStream_t)stream;
-    if ((rc = clear_flag(flag, st))) return rc;
-    if (p->chunks > 0) {
-        const dim3 grid((unsigned)p->chunks), block(kBlock);
-        launch_reduce(p, s, flag, st);
-        if ((rc = launched("reduce_kernel"))) return rc;
-        hipLaunchKernelGGL((lamb_phase1_from_sum_kernel<kBlock>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, p->d_partials, flag);
-        if ((rc = launched("lamb_phase1_kernel"))) return rc;
+    if (p->chunks == 0) {
+        if ((rc = clear_flag(flag, st))) return rc;
+        return lamb_norms(p, st);
     }
+    const dim3 grid((unsigned)p->chunks);
+    BY_BLOCK(p, launch_reduce<BLK>(p, s, flag, st));
+    if ((rc = launched("reduce_kernel"))) return rc;
+    BY_BLOCK(p, hipLaunchKernelGGL((lamb_phase1_from_sum_kernel<BLK>), grid, dim3(BLK), 0, st, p->d_tensors, p->d_chunks, s, p->d_partials));
+    if ((rc = launched("lamb_phase1_from_sum_kernel"))) return rc;
     if ((rc = lamb_norms(p, st))) return rc;
     if ((rc = lamb_phase2_impl(p, s, flag, st, false))) return rc;
-    if (p->chunks > 0) {
-        const dim3 grid((unsigned)p->chunks), block(kBlock);
-        hipLaunchKernelGGL((cast_kernel<kBlock>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag, 1);
-        return launched("cast_kernel");
-    }
-    return CC_OK;
+    return cast_launch(p, s, flag, st, 1);
 }
 
 int cc_copy_probe(void *dst, const void *src, uint64_t bytes, void *stream)
