@@ -52,6 +52,7 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=2, help="workload configuration 1..5 (default 2, the metric's)")
     ap.add_argument("--chunk-elems", type=int, default=0)
     ap.add_argument("--in-place", action="store_true", help="in-place state with the per-element guard (skip_mode 1)")
+    ap.add_argument("--flat", action="store_true", help="the same number of parameters as ONE contiguous tensor (Table 2's single-tensor case)")
     ap.add_argument("--graph", action="store_true", help="enqueue the timed steps as replays of a captured HIP graph of 20 steps")
     ap.add_argument("--no-extras", action="store_true", help="only the headline step (for profiling runs)")
     ap.add_argument("--copy-only", action="store_true", help="run only the plain copy kernel (2 GiB, 20 launches): counter calibration")
@@ -85,6 +86,9 @@ def main() -> int:
         print(json.dumps({"copy_only": True, "bytes_read_per_launch": nbytes, "bytes_written_per_launch": nbytes, "launches": 20}))
         return 0
     cfg = W.config(args.config)
+    if args.flat:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, params=(W.ParamSpec("flat", cfg.numel, "matrix"),))
     R, N = cfg.R, cfg.numel
     K, Wm = args.steps, args.warmup
 
@@ -157,6 +161,7 @@ def main() -> int:
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "config %d: fused %s, %s, T=%d tensors, N=%d fp32 params, R=%d fp16 gradient slices, "
                                "%s state" % (cfg.index, cfg.optimizer,
+                                             "the same N as ONE contiguous tensor" if args.flat else
                                              {1: "one flat tensor", 2: "BERT-Large parameter list", 3: "BERT-Large parameter list",
                                               4: "GPT-2 1.5B parameter list", 5: "1/8 shard of an 8.3B transformer"}[cfg.index],
                                              len(cfg.params), N, R, "in-place" if args.in_place else "out-of-place (ping-pong)"),

@@ -99,7 +99,7 @@ int64_t cc_chunk_table_fill(const uint64_t *numels, int32_t T, int32_t chunk_ele
                             uint32_t *table, int64_t capacity);
 
 /* Default chunk size in elements for large shards (a tuning choice of this library; the paper's buckets hold
- * 2^10).  Shards below 4 Mi elements default to 1024-element chunks, for more workgroups. */
+ * 2^10).  Shards below 64 Mi elements default to 1024-element chunks (faster there in the size sweep). */
 int32_t cc_default_chunk_elems(void);
 
 /* ---- plan ---- */

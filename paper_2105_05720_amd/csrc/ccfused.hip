@@ -18,7 +18,7 @@ namespace {
 
 constexpr int32_t kDefaultChunkElems = 4096;     // one sweep of a 512-thread workgroup (2 groups x 512 lanes x 4 elements)
 constexpr int32_t kSmallChunkElems = 1024;       // one sweep of a 128-thread workgroup: more workgroups for small shards
-constexpr uint64_t kSmallShardElems = 4u << 20;  // below this many elements the default chunk is the small one
+constexpr uint64_t kSmallShardElems = 64u << 20; // below this many elements the default chunk is the small one (size sweep)
 constexpr int32_t kMaxChunkElems = 1 << 24;      // lane offsets inside a chunk are 32-bit byte offsets
 constexpr int kBigBlock = 512, kSmallBlock = 128;
 
