@@ -245,8 +245,10 @@ def cpu_baseline(shard, cfg, ghp, target_seconds):
                                     grads=[bits(shard.grad_of(r, k)) for r in range(cfg.R)],
                                     weight_decay=shard.wds[k]) for k in ks]
 
-    # sample: tensors of about equal size so that threads stay busy; skip the giant embeddings
-    order = [k for k, s in enumerate(cfg.params) if 0 < s.numel <= 8_000_000] or list(range(len(cfg.params)))
+    # calibrate on a few small tensors, then take tensors in list order (the giant embeddings last, they keep
+    # one thread busy on their own) until the time budget is filled or the list ends
+    small = [k for k, s in enumerate(cfg.params) if 0 < s.numel <= 8_000_000]
+    order = small + [k for k, s in enumerate(cfg.params) if s.numel > 8_000_000]
     calib = []
     budget = 2_000_000
     for k in order:
@@ -261,10 +263,10 @@ def cpu_baseline(shard, cfg, ghp, target_seconds):
     want = rate * target_seconds
     sample, total = [], 0
     for k in order:
-        sample.append(k)
-        total += cfg.params[k].numel
         if total >= want:
             break
+        sample.append(k)
+        total += cfg.params[k].numel
     ots = tensors_of(sample)
     t0 = time.perf_counter()
     step_fn(ots, ohp, threads=threads)
@@ -272,7 +274,8 @@ def cpu_baseline(shard, cfg, ghp, target_seconds):
     bpp = adam_bytes_per_param(cfg.R) if cfg.optimizer == "adam" else lamb_bytes_per_param(cfg.R)
     return {"value": round(bpp * total / dt / 1e9, 4), "unit": "GB/s", "params_per_sec": round(total / dt, 1),
             "cores": threads, "kind": "oracle", "seconds": round(dt, 2),
-            "sample": "first %d tensors (<= 8M elements each) of the same list, %d params, one %s step" % (len(sample), total, cfg.optimizer)}
+            "sample": "%d of the %d tensors of the same list (%d params), one %s step, whole tensors spread over %d threads" % (
+                len(sample), len(cfg.params), total, cfg.optimizer, threads)}
 
 
 if __name__ == "__main__":

@@ -74,12 +74,19 @@ uint16_t oracle_float_to_half(float x)
 
 /* ---- the reduced gradient of one element ---- */
 
-static double reduced_sum(const uint16_t *const *g, int R, uint64_t i)
+/* The R slices hold fp16 bit patterns (mixed precision, the paper's main case) or, with grad_f32, fp32 values
+ * (Section 6.1.1 reports Float 32 as qualitatively similar). */
+static double reduced_sum(const void *const *g, int grad_f32, int R, uint64_t i)
 {
     double S = 0.0;
-    for (int r = 0; r < R; ++r) S += oracle_half_to_double(g[r][i]);   /* the "+" all-reduce of Fig. 4a */
+    for (int r = 0; r < R; ++r)                                        /* the "+" all-reduce of Fig. 4a */
+        S += grad_f32 ? (double)((const float *)g[r])[i] : oracle_half_to_double(((const uint16_t *)g[r])[i]);
     return S;
 }
+
+/* The overflow decision is taken on the sum as an fp32 value, the precision the GPU path reduces in: fp16 slices
+ * cannot overflow it, fp32 slices can. */
+static int sum_overflows(double S) { return !isfinite((float)S); }
 
 static double unscale_divisor(float loss_scale, int R, int grad_average)
 {
@@ -87,11 +94,11 @@ static double unscale_divisor(float loss_scale, int R, int grad_average)
 }
 
 /* 1 if any reduced gradient of this tensor is inf or NaN, else 0. */
-int oracle_grad_overflow(uint64_t n, int R, const uint16_t *const *g)
+int oracle_grad_overflow(uint64_t n, int R, const void *const *g, int grad_f32)
 {
     int bad = 0;
     for (uint64_t i = 0; i < n; ++i)
-        if (!isfinite(reduced_sum(g, R, i))) bad = 1;
+        if (sum_overflows(reduced_sum(g, grad_f32, R, i))) bad = 1;
     return bad;
 }
 
@@ -108,7 +115,7 @@ void oracle_keep_tensor(uint64_t n, const float *w, const float *m, const float 
 /* ---- Adam on one tensor of the slice (Fig. 4a) ----
  * adam_mode 1: decoupled decay, u += wd*w.   adam_mode 0: L2, g += wd*w before the moments.
  * guard_elements != 0: an element whose reduced gradient is not finite keeps its inputs. */
-void oracle_adam_tensor(uint64_t n, int R, const uint16_t *const *g,
+void oracle_adam_tensor(uint64_t n, int R, const void *const *g, int grad_f32,
                         const float *w, const float *m, const float *v,
                         float *w_out, float *m_out, float *v_out, uint16_t *w16_out,
                         float lr_f, float beta1_f, float beta2_f, float eps_f, float wd_f,
@@ -120,8 +127,8 @@ void oracle_adam_tensor(uint64_t n, int R, const uint16_t *const *g,
     const double c1 = 1.0 - pow(beta1, (double)step);
     const double c2 = 1.0 - pow(beta2, (double)step);
     for (uint64_t i = 0; i < n; ++i) {
-        const double S = reduced_sum(g, R, i);
-        if (guard_elements && !isfinite(S)) {
+        const double S = reduced_sum(g, grad_f32, R, i);
+        if (guard_elements && sum_overflows(S)) {
             w_out[i] = w[i]; m_out[i] = m[i]; v_out[i] = v[i];
             w16_out[i] = oracle_float_to_half(w[i]);
             continue;
@@ -145,7 +152,7 @@ void oracle_adam_tensor(uint64_t n, int R, const uint16_t *const *g,
 
 /* ---- LAMB on one tensor of the slice ----
  * Returns the two norms through norms[0] = ||w||, norms[1] = ||u|| (may be NULL). */
-void oracle_lamb_tensor(uint64_t n, int R, const uint16_t *const *g,
+void oracle_lamb_tensor(uint64_t n, int R, const void *const *g, int grad_f32,
                         const float *w, const float *m, const float *v,
                         float *w_out, float *m_out, float *v_out, uint16_t *w16_out,
                         float lr_f, float beta1_f, float beta2_f, float eps_f, float wd_f,
@@ -158,7 +165,7 @@ void oracle_lamb_tensor(uint64_t n, int R, const uint16_t *const *g,
     double sum_w2 = 0.0, sum_u2 = 0.0;
     /* first sweep: moments, and the two sums of squares over this rank's elements */
     for (uint64_t i = 0; i < n; ++i) {
-        const double gh = reduced_sum(g, R, i) / div;
+        const double gh = reduced_sum(g, grad_f32, R, i) / div;
         const double wi = w[i];
         const double m_ = (double)m[i] * beta1 + (1.0 - beta1) * gh;
         const double v_ = (double)v[i] * beta2 + (1.0 - beta2) * gh * gh;
@@ -173,7 +180,7 @@ void oracle_lamb_tensor(uint64_t n, int R, const uint16_t *const *g,
     if (norms) { norms[0] = norm_w; norms[1] = norm_u; }
     /* second sweep: the same u, scaled by the tensor's ratio */
     for (uint64_t i = 0; i < n; ++i) {
-        const double gh = reduced_sum(g, R, i) / div;
+        const double gh = reduced_sum(g, grad_f32, R, i) / div;
         const double wi = w[i];
         const double m_ = (double)m[i] * beta1 + (1.0 - beta1) * gh;
         const double v_ = (double)v[i] * beta2 + (1.0 - beta2) * gh * gh;

@@ -37,6 +37,7 @@ def build(force: bool = False) -> str:
 _f32p = C.POINTER(C.c_float)
 _u16p = C.POINTER(C.c_uint16)
 _u16pp = C.POINTER(_u16p)
+_vpp = C.POINTER(C.c_void_p)
 
 
 def _load():
@@ -50,10 +51,10 @@ def _load():
         lib.oracle_float_to_half.restype = C.c_uint16
         lib.oracle_float_to_half.argtypes = [C.c_float]
         lib.oracle_grad_overflow.restype = C.c_int
-        lib.oracle_grad_overflow.argtypes = [C.c_uint64, C.c_int, _u16pp]
+        lib.oracle_grad_overflow.argtypes = [C.c_uint64, C.c_int, _vpp, C.c_int]
         lib.oracle_keep_tensor.restype = None
         lib.oracle_keep_tensor.argtypes = [C.c_uint64, _f32p, _f32p, _f32p, _f32p, _f32p, _f32p, _u16p]
-        common = [C.c_uint64, C.c_int, _u16pp, _f32p, _f32p, _f32p, _f32p, _f32p, _f32p, _u16p,
+        common = [C.c_uint64, C.c_int, _vpp, C.c_int, _f32p, _f32p, _f32p, _f32p, _f32p, _f32p, _u16p,
                   C.c_float, C.c_float, C.c_float, C.c_float, C.c_float, C.c_float, C.c_int, C.c_int]
         lib.oracle_adam_tensor.restype = None
         lib.oracle_adam_tensor.argtypes = common + [C.c_int, C.c_int]
@@ -79,7 +80,7 @@ class Hyper:
 
 @dataclass
 class OracleTensor:
-    """One tensor of the slice: fp32 state, R fp16 gradient slices as uint16 bit patterns."""
+    """One tensor of the slice: fp32 state; R gradient slices, all uint16 (fp16 bit patterns) or all float32."""
     w: np.ndarray
     m: np.ndarray
     v: np.ndarray
@@ -104,11 +105,13 @@ def _u16(a: np.ndarray):
 
 
 def _gptrs(grads: Sequence[np.ndarray], n: int):
-    arr = (_u16p * len(grads))()
+    """(array of R pointers, 1 if the slices are fp32 else 0)"""
+    f32 = int(grads[0].dtype == np.float32)
+    arr = (C.c_void_p * len(grads))()
     for r, g in enumerate(grads):
-        assert g.dtype == np.uint16 and g.flags.c_contiguous and g.size == n
-        arr[r] = g.ctypes.data_as(_u16p)
-    return arr
+        assert g.dtype == (np.float32 if f32 else np.uint16) and g.flags.c_contiguous and g.size == n
+        arr[r] = g.ctypes.data
+    return arr, f32
 
 
 def _alloc_outputs(t: OracleTensor):
@@ -129,7 +132,8 @@ def float_to_half(x: float) -> int:
 
 def grad_overflow(grads: Sequence[np.ndarray]) -> int:
     n = grads[0].size
-    return int(_load().oracle_grad_overflow(n, len(grads), _gptrs(grads, n)))
+    ptrs, f32 = _gptrs(grads, n)
+    return int(_load().oracle_grad_overflow(n, len(grads), ptrs, f32))
 
 
 def _map(fn, tensors, threads):
@@ -159,7 +163,8 @@ def adam_step(tensors: List[OracleTensor], hp: Hyper, threads: int = 1) -> int:
 
     def one(t: OracleTensor):
         n = t.w.size
-        lib.oracle_adam_tensor(n, len(t.grads), _gptrs(t.grads, n), _f32(t.w), _f32(t.m), _f32(t.v),
+        ptrs, f32 = _gptrs(t.grads, n)
+        lib.oracle_adam_tensor(n, len(t.grads), ptrs, f32, _f32(t.w), _f32(t.m), _f32(t.v),
                                _f32(t.w_out), _f32(t.m_out), _f32(t.v_out), _u16(t.w16_out),
                                hp.lr, hp.beta1, hp.beta2, hp.eps, t.weight_decay, hp.loss_scale,
                                hp.step, hp.grad_average, hp.adam_mode, int(hp.skip_mode == 1))
@@ -182,7 +187,8 @@ def lamb_step(tensors: List[OracleTensor], hp: Hyper, threads: int = 1) -> int:
     def one(t: OracleTensor):
         n = t.w.size
         norms = (C.c_double * 2)()
-        lib.oracle_lamb_tensor(n, len(t.grads), _gptrs(t.grads, n), _f32(t.w), _f32(t.m), _f32(t.v),
+        ptrs, f32 = _gptrs(t.grads, n)
+        lib.oracle_lamb_tensor(n, len(t.grads), ptrs, f32, _f32(t.w), _f32(t.m), _f32(t.v),
                                _f32(t.w_out), _f32(t.m_out), _f32(t.v_out), _u16(t.w16_out),
                                hp.lr, hp.beta1, hp.beta2, hp.eps, t.weight_decay, hp.loss_scale,
                                hp.step, hp.grad_average, norms)

@@ -476,23 +476,34 @@ __global__ __launch_bounds__(BLOCK) void lamb_phase1_from_sum_kernel(const DevTe
     lamb_phase1_body<GradSum, false, BLOCK>(tensors, chunks, s, partials, nullptr, nullptr);
 }
 
-// LAMB second level: one workgroup per tensor adds that tensor's chunk partials in a fixed order.
-constexpr int kNormBlock = 256;
+// LAMB second level: one workgroup per tensor adds that tensor's chunk partials in a fixed order (four
+// independent strided partial sums per thread, then the block sum), so the result does not change between runs.
+constexpr int kNormBlock = 1024;
 __global__ __launch_bounds__(kNormBlock) void lamb_norms_kernel(const DevTensor *__restrict__ tensors,
                                                                 const double *__restrict__ partials,
                                                                 double *__restrict__ sums)
 {
     const DevTensor *t = tensors + blockIdx.x;
     const uint32_t first = t->first_chunk, n = t->num_chunks;
-    double a = 0.0, b = 0.0;
-    for (uint32_t c = threadIdx.x; c < n; c += kNormBlock) {
-        a += partials[2 * (uint64_t)(first + c)];
-        b += partials[2 * (uint64_t)(first + c) + 1];
+    const double *p = partials + 2 * (uint64_t)first;
+    double a[4] = {0.0, 0.0, 0.0, 0.0}, b[4] = {0.0, 0.0, 0.0, 0.0};
+    uint32_t c = threadIdx.x;
+    for (; c + 3 * kNormBlock < n; c += 4 * kNormBlock) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            a[k] += p[2 * (uint64_t)(c + k * kNormBlock)];
+            b[k] += p[2 * (uint64_t)(c + k * kNormBlock) + 1];
+        }
     }
-    block_sum2<kNormBlock>(a, b);
+    for (int k = 0; c < n; c += kNormBlock, ++k) {
+        a[k] += p[2 * (uint64_t)c];
+        b[k] += p[2 * (uint64_t)c + 1];
+    }
+    double sa = (a[0] + a[1]) + (a[2] + a[3]), sb = (b[0] + b[1]) + (b[2] + b[3]);
+    block_sum2<kNormBlock>(sa, sb);
     if (threadIdx.x == 0) {
-        sums[2 * (uint64_t)blockIdx.x] = a;
-        sums[2 * (uint64_t)blockIdx.x + 1] = b;
+        sums[2 * (uint64_t)blockIdx.x] = sa;
+        sums[2 * (uint64_t)blockIdx.x + 1] = sb;
     }
 }
 

@@ -19,13 +19,15 @@ MUTANTS = [
     ("update sign", "const double p_ = wi - lr * u;", "const double p_ = wi + lr * u;", 0),
     ("decoupled decay dropped", "if (adam_mode != 0) u += wd * wi;", "", 0),
     ("L2 decay dropped", "if (adam_mode == 0) gh += wd * wi;", "", 0),
-    ("only the last rank is kept", "S += oracle_half_to_double(g[r][i]);", "S = oracle_half_to_double(g[r][i]);", 0),
+    ("only the last rank is kept", "S += grad_f32 ?", "S = grad_f32 ?", 0),
+    ("fp32 slices read as halves", "grad_f32 ? (double)((const float *)g[r])[i]", "0 ? (double)((const float *)g[r])[i]", 0),
+    ("flag decided in double", "return !isfinite((float)S);", "return !isfinite(S);", 0),
     ("step off by one", "pow(beta1, (double)step)", "pow(beta1, (double)(step + 1))", 0),
     ("gradient not squared", "(double)v[i] * beta2 + (1.0 - beta2) * gh * gh;\n        const double m1", "(double)v[i] * beta2 + (1.0 - beta2) * gh;\n        const double m1", 0),
     ("loss scale multiplies", "double gh = S / div;", "double gh = S * div;", 0),
     ("average ignored", "(grad_average ? (double)R : 1.0)", "1.0", 0),
-    ("flag ignores infinities", "if (!isfinite(reduced_sum(g, R, i))) bad = 1;", "if (isnan(reduced_sum(g, R, i))) bad = 1;", 0),
-    ("guard keeps nothing", "if (guard_elements && !isfinite(S)) {", "if (0) {", 0),
+    ("flag ignores infinities", "return !isfinite((float)S);", "return isnan((float)S);", 0),
+    ("guard keeps nothing", "if (guard_elements && sum_overflows(S)) {", "if (0) {", 0),
     ("trust ratio inverted", "norm_w / norm_u : 1.0", "norm_u / norm_w : 1.0", 0),
     ("trust ratio fallback", "norm_w / norm_u : 1.0", "norm_w / norm_u : 0.0", 0),
     ("norm of u without decay", "+ eps) + wd * wi;\n        sum_w2", "+ eps);\n        sum_w2", 0),

@@ -368,3 +368,60 @@ def test_lamb_ratio_is_per_tensor():
     r = [h.norms[0] / h.norms[1] for h in halves]
     assert r[1] / r[0] == pytest.approx(10.0, rel=0.2)
     assert not np.array_equal(whole.w_out[:300], halves[0].w_out)
+
+
+# ----------------------------------------------------------------------------- fp32 gradient slices
+
+def test_fp32_gradients_one_rank_equals_torch_float64():
+    """The same Adam program with fp32 gradient slices (the paper's Float 32 case, Section 6.1.1)."""
+    rng = np.random.default_rng(31)
+    n = 4096
+    w, m, v, _ = _random_case(rng, n, 1)
+    g = f32(rng.normal(0, 1e-2, n))
+    for mode, cls in ((1, torch.optim.AdamW), (0, torch.optim.Adam)):
+        hp = Hyper(lr=2e-3, step=3, adam_mode=mode)
+        ot = make_tensor(w, [g], m, v, 0.01)
+        assert oracle.adam_step([ot], hp) == 0
+        tw, tm, tv = _torch_adam_step(cls, w, m, v, g.astype(np.float64), hp, 0.01, 3)
+        for got, want in ((ot.w_out, tw), (ot.m_out, tm), (ot.v_out, tv)):
+            assert ulp_f32(got, want.astype(np.float32)).max() <= 1
+
+
+def test_fp32_gradients_sum_and_match_the_fp16_path_on_fp16_values():
+    """fp32 slices that hold fp16-representable values give exactly what the fp16 slices give; R identical
+    slices sum to R g; and the two oracles agree for LAMB too."""
+    rng = np.random.default_rng(32)
+    n, R = 3000, 8
+    w, m, v, grads = _random_case(rng, n, R)
+    as_f32 = [bits_to_f64(g).astype(np.float32) for g in grads]
+    hp = Hyper(step=2, loss_scale=4.0)
+    for step_fn in (oracle.adam_step, oracle.lamb_step):
+        a = make_tensor(w, grads, m, v, 0.01)
+        b = make_tensor(w, as_f32, m, v, 0.01)
+        assert step_fn([a], hp) == step_fn([b], hp) == 0
+        for x, y in ((a.w_out, b.w_out), (a.m_out, b.m_out), (a.v_out, b.v_out), (a.w16_out, b.w16_out)):
+            assert np.array_equal(x, y)
+    g = f32(rng.normal(0, 1e-2, n))
+    ot = make_tensor(w, [g.copy() for _ in range(R)], wd=0.0)
+    oracle.adam_step([ot], Hyper(step=1))
+    b1 = F(0.9)
+    assert np.array_equal(ot.m_out, ((1 - b1) * R * g.astype(np.float64)).astype(np.float32))
+
+
+def test_fp32_gradient_overflow_is_decided_on_the_fp32_sum():
+    big = np.float32(3e38)
+    n = 8
+    w = f32(np.full(n, 0.01))
+    fine = [f32(np.full(n, 1.0)), f32(np.full(n, 2.0))]
+    assert oracle.grad_overflow(fine) == 0
+    over = [f32(np.full(n, big)), f32(np.full(n, big))]          # 6e38 is finite in double, infinite in fp32
+    assert oracle.grad_overflow(over) == 1
+    inf = [f32(np.full(n, 1.0)), f32(np.full(n, 1.0))]
+    inf[1][3] = np.inf
+    assert oracle.grad_overflow(inf) == 1
+    nan = [f32(np.full(n, 1.0))]
+    nan[0][7] = np.nan
+    assert oracle.grad_overflow(nan) == 1
+    t = make_tensor(w, over)
+    assert oracle.adam_step([t], Hyper(step=1)) == 1
+    assert np.array_equal(t.w_out, w)

@@ -25,7 +25,9 @@ def make_tensor(w, grads_bits, m=None, v=None, wd=0.0):
     w = f32(w)
     m = np.zeros_like(w) if m is None else f32(m)
     v = np.zeros_like(w) if v is None else f32(v)
-    grads = [np.ascontiguousarray(np.asarray(g, dtype=np.uint16)) for g in grads_bits]
+    # uint16 arrays are fp16 bit patterns; float32 arrays are fp32 gradient slices
+    grads = [np.ascontiguousarray(g) if getattr(g, "dtype", None) == np.float32 else np.ascontiguousarray(np.asarray(g, dtype=np.uint16))
+             for g in grads_bits]
     return oracle.OracleTensor(w=w, m=m, v=v, grads=grads, weight_decay=wd)
 
 
