@@ -28,20 +28,23 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MEASURED_TRAFFIC_BYTES = {2: 9.4256e9 + 4.7069e9}
 
 
+GRAD_BYTES = 2                 # bytes per gradient element (set to 4 by --grad-dtype f32)
+
+
 def adam_bytes_per_param(R):   # read 2R (fp16 grads) + 12 (w, m, v); write 12 (w, m, v) + 2 (fp16 w)
-    return 2 * R + 26
+    return GRAD_BYTES * R + 26
 
 
 def lamb_bytes_per_param(R):   # phase 1: read 2R + 12, write 8; phase 2: read 12, write 6
-    return 2 * R + 38
+    return GRAD_BYTES * R + 38
 
 
 def unfused_adam_bytes_per_param(R):   # reduce: 2R + 4; optimizer: 16 + 12; cast: 4 + 2
-    return 2 * R + 38
+    return GRAD_BYTES * R + 38
 
 
 def unfused_lamb_bytes_per_param(R):   # reduce 2R + 4; phase 1: 16 + 8; phase 2: 12 + 4; cast 4 + 2
-    return 2 * R + 50
+    return GRAD_BYTES * R + 50
 
 
 def main() -> int:
@@ -52,6 +55,7 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=2, help="workload configuration 1..5 (default 2, the metric's)")
     ap.add_argument("--chunk-elems", type=int, default=0)
     ap.add_argument("--in-place", action="store_true", help="in-place state with the per-element guard (skip_mode 1)")
+    ap.add_argument("--grad-dtype", choices=("f16", "f32"), default="f16", help="element type of the R gradient slices")
     ap.add_argument("--flat", action="store_true", help="the same number of parameters as ONE contiguous tensor (Table 2's single-tensor case)")
     ap.add_argument("--graph", action="store_true", help="enqueue the timed steps as replays of a captured HIP graph of 20 steps")
     ap.add_argument("--no-extras", action="store_true", help="only the headline step (for profiling runs)")
@@ -92,8 +96,11 @@ def main() -> int:
     R, N = cfg.R, cfg.numel
     K, Wm = args.steps, args.warmup
 
+    global GRAD_BYTES
+    GRAD_BYTES = 2 if args.grad_dtype == "f16" else 4
     shard = Shard([s.numel for s in cfg.params], [cfg.wd_of(s) for s in cfg.params], R, device=dev,
-                  chunk_elems=args.chunk_elems, in_place=args.in_place)
+                  chunk_elems=args.chunk_elems, in_place=args.in_place,
+                  grad_dtype=torch.float16 if args.grad_dtype == "f16" else torch.float32)
     W.fill_state(shard, cfg)
     W.fill_grads(shard, cfg, 1)
     torch.cuda.synchronize()
@@ -164,13 +171,15 @@ def main() -> int:
                                              "the same N as ONE contiguous tensor" if args.flat else
                                              {1: "one flat tensor", 2: "BERT-Large parameter list", 3: "BERT-Large parameter list",
                                               4: "GPT-2 1.5B parameter list", 5: "1/8 shard of an 8.3B transformer"}[cfg.index],
-                                             len(cfg.params), N, R, "in-place" if args.in_place else "out-of-place (ping-pong)"),
+                                             len(cfg.params), N, R, "in-place" if args.in_place else "out-of-place (ping-pong)") + (
+                                                 " [fp32 gradient slices]" if args.grad_dtype == "f32" else ""),
                    "chunk_elems": (N + chunks - 1) // chunks if cfg.index == 1 and chunks else (args.chunk_elems or cc.cc_default_chunk_elems()),
                    "chunks": chunks, "launch": "hip graph replay" if args.graph else "eager",
                    "table_bytes": table_bytes, "algorithmic_bytes_per_param": bpp},
         "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(gbs / HBM_PEAK_GBS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.index) if (args.chunk_elems == 0 and not args.in_place) else None,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.index) if (args.chunk_elems == 0 and not args.in_place and not args.flat
+                                                                         and args.grad_dtype == "f16") else None,
                      "kernel": "fused_adam_kernel<R=%d>" % R if cfg.optimizer == "adam" else "lamb_phase1_kernel + lamb_phase2_kernel",
                      "bytes_per_launch": bpp * N, "avg_launch_ms": round(ms, 5)},
     }

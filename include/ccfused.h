@@ -61,7 +61,8 @@ typedef struct cc_tensor {
     float          *m_out;
     float          *v_out;
     uint16_t       *w16_out;           /* fp16 copy of w_out, round to nearest even (what is all-gathered) */
-    const uint16_t *grad[CC_MAX_R];    /* R fp16 gradient slices, one per contributing rank */
+    const void     *grad[CC_MAX_R];    /* R gradient slices, one per contributing rank: fp16 bit patterns, or fp32
+                                          values when the plan is created with CC_GRAD_F32 */
     float           weight_decay;      /* per tensor (0 for bias / LayerNorm) */
 } cc_tensor;
 
@@ -84,6 +85,10 @@ typedef struct cc_hparams {
                                   1: per-element guard: an element whose reduced gradient is inf/NaN
                                      keeps its w, m, v; allowed in place.  LAMB: 0 only */
 } cc_hparams;
+
+/* Element type of the incoming gradient slices.  fp16 is the mixed-precision case the paper evaluates; fp32 is
+ * its "Float 32" case (Section 6.1.1).  With fp32 slices the flag also rises when a finite sum overflows fp32. */
+typedef enum cc_grad_dtype { CC_GRAD_F16 = 0, CC_GRAD_F32 = 1 } cc_grad_dtype;
 
 typedef struct cc_plan cc_plan;   /* opaque: device copy of the tensor list, chunk table, scratch */
 
@@ -113,6 +118,10 @@ int32_t cc_default_chunk_elems(void);
  * must stay valid while the plan is used.  Tensors with numel == 0 are legal and produce no chunks.
  */
 int cc_plan_create(const cc_tensor *tensors, int32_t T, int32_t R, int32_t chunk_elems, cc_plan **out);
+
+/* The same with the gradient element type stated (cc_plan_create is the CC_GRAD_F16 case). */
+int cc_plan_create_ex(const cc_tensor *tensors, int32_t T, int32_t R, int32_t chunk_elems, int32_t grad_dtype,
+                      cc_plan **out);
 int cc_plan_destroy(cc_plan *plan);
 
 /* Totals of a plan: elements, chunks and bytes of table memory on the device. */

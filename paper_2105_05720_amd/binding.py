@@ -11,6 +11,7 @@ from dataclasses import dataclass, field
 from typing import List, Optional, Sequence
 
 CC_MAX_R = 16
+CC_GRAD_F16, CC_GRAD_F32 = 0, 1
 CC_OK, CC_ERR_NULL, CC_ERR_ARG, CC_ERR_ALIGN, CC_ERR_ALIAS, CC_ERR_HIP, CC_ERR_NOMEM = 0, -1, -2, -3, -4, -5, -6
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -45,6 +46,7 @@ EXPORTS = {
     "cc_chunk_table_fill": (C.c_int64, [C.POINTER(C.c_uint64), C.c_int32, C.c_int32, C.POINTER(C.c_uint32), C.c_int64]),
     "cc_default_chunk_elems": (C.c_int32, []),
     "cc_plan_create": (C.c_int, [C.POINTER(cc_tensor), C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_void_p)]),
+    "cc_plan_create_ex": (C.c_int, [C.POINTER(cc_tensor), C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_void_p)]),
     "cc_plan_destroy": (C.c_int, [C.c_void_p]),
     "cc_plan_info": (C.c_int, [C.c_void_p, C.POINTER(C.c_uint64), C.POINTER(C.c_int64), C.POINTER(C.c_uint64)]),
     "cc_fused_adam_step": (C.c_int, [C.c_void_p, C.POINTER(cc_hparams), C.c_void_p, C.c_void_p]),
@@ -178,6 +180,10 @@ def cc_chunk_table_fill(numels: Sequence[int], chunk_elems: int = 0, capacity: O
 # ---- plan ----
 
 def cc_plan_create(tensors: Sequence[Tensor], R: int, chunk_elems: int = 0) -> Plan:
+    return cc_plan_create_ex(tensors, R, chunk_elems, CC_GRAD_F16)
+
+
+def cc_plan_create_ex(tensors: Sequence[Tensor], R: int, chunk_elems: int = 0, grad_dtype: int = CC_GRAD_F16) -> Plan:
     arr = (cc_tensor * max(len(tensors), 1))()
     for i, t in enumerate(tensors):
         c = arr[i]
@@ -189,7 +195,7 @@ def cc_plan_create(tensors: Sequence[Tensor], R: int, chunk_elems: int = 0) -> P
             c.grad[r] = _ptr(g)
         c.weight_decay = t.weight_decay
     handle = C.c_void_p()
-    _check(load().cc_plan_create(arr, len(tensors), R, chunk_elems, C.byref(handle)))
+    _check(load().cc_plan_create_ex(arr, len(tensors), R, chunk_elems, grad_dtype, C.byref(handle)))
     return Plan(handle.value, list(tensors))
 
 

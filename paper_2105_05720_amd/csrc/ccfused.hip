@@ -66,6 +66,7 @@ struct cc_plan {
     int64_t chunks = 0;
     uint64_t numel = 0;
     bool in_place = false;                  // some tensor has out == in
+    bool grad_f32 = false;                  // gradient slices are fp32 instead of fp16
     std::vector<DevTensor> host_tensors;    // host mirror of the device descriptors
     std::vector<uint64_t> gsum_offset;      // element offset of each tensor in the unfused fp32 buffer
     uint64_t gsum_elems = 0;
@@ -118,11 +119,17 @@ int64_t cc_chunk_table_fill(const uint64_t *numels, int32_t T, int32_t chunk_ele
 
 int cc_plan_create(const cc_tensor *tensors, int32_t T, int32_t R, int32_t chunk_elems, cc_plan **out)
 {
+    return cc_plan_create_ex(tensors, T, R, chunk_elems, CC_GRAD_F16, out);
+}
+
+int cc_plan_create_ex(const cc_tensor *tensors, int32_t T, int32_t R, int32_t chunk_elems, int32_t grad_dtype, cc_plan **out)
+{
     if (!out) return fail(CC_ERR_NULL, "cc_plan_create: out is NULL");
     *out = nullptr;
     if (!tensors) return fail(CC_ERR_NULL, "cc_plan_create: tensors is NULL");
     if (T <= 0) return fail(CC_ERR_ARG, "cc_plan_create: T = %d must be positive", T);
     if (R < 1 || R > CC_MAX_R) return fail(CC_ERR_ARG, "cc_plan_create: R = %d outside 1..%d", R, CC_MAX_R);
+    if (grad_dtype != CC_GRAD_F16 && grad_dtype != CC_GRAD_F32) return fail(CC_ERR_ARG, "cc_plan_create: grad_dtype = %d", grad_dtype);
     if (resolve_chunk(chunk_elems) < 0) return fail(CC_ERR_ARG, "chunk_elems = %d is not a positive multiple of 1024 up to 2^24", chunk_elems);
     uint64_t total_elems = 0;
     for (int32_t t = 0; t < T; ++t) total_elems += tensors[t].numel;
@@ -157,6 +164,7 @@ int cc_plan_create(const cc_tensor *tensors, int32_t T, int32_t R, int32_t chunk
     if (!p) return fail(CC_ERR_NOMEM, "cc_plan_create: out of host memory");
     p->T = T; p->R = R; p->chunk_elems = ce; p->chunks = chunks; p->in_place = in_place;
     p->block = ce >= kDefaultChunkElems ? kBigBlock : kSmallBlock;
+    p->grad_f32 = grad_dtype == CC_GRAD_F32;
     std::vector<uint32_t> table;
     try {
         p->host_tensors.resize((size_t)T);
@@ -313,12 +321,30 @@ int ensure_gsum(cc_plan *p)
         else { constexpr int BLK = kSmallBlock; CALL; }                       \
     } while (0)
 
-template <int MODE, int BLK>
-void launch_fused_adam(const cc_plan *p, const StepScalars &s, int32_t *flag, hipStream_t st)
+template <int MODE, int BLK, bool GF32>
+void launch_fused_adam_r(const cc_plan *p, const StepScalars &s, int32_t *flag, hipStream_t st)
 {
     const dim3 grid((unsigned)p->chunks), block(BLK);
     switch (p->R) {
-#define CASE(r) case r: hipLaunchKernelGGL((fused_adam_kernel<r, MODE, BLK>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, p->d_flag_scratch, flag); break;
+#define CASE(r) case r: hipLaunchKernelGGL((fused_adam_kernel<r, MODE, BLK, GF32>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, p->d_flag_scratch, flag); break;
+        FOR_EACH_R(CASE)
+#undef CASE
+    }
+}
+
+template <int MODE, int BLK>
+void launch_fused_adam(const cc_plan *p, const StepScalars &s, int32_t *flag, hipStream_t st)
+{
+    if (p->grad_f32) launch_fused_adam_r<MODE, BLK, true>(p, s, flag, st);
+    else launch_fused_adam_r<MODE, BLK, false>(p, s, flag, st);
+}
+
+template <int BLK, bool GF32>
+void launch_lamb_phase1_r(const cc_plan *p, const StepScalars &s, int32_t *flag, hipStream_t st)
+{
+    const dim3 grid((unsigned)p->chunks), block(BLK);
+    switch (p->R) {
+#define CASE(r) case r: hipLaunchKernelGGL((lamb_phase1_kernel<r, BLK, GF32>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, p->d_partials, p->d_flag_scratch, flag); break;
         FOR_EACH_R(CASE)
 #undef CASE
     }
@@ -327,9 +353,16 @@ void launch_fused_adam(const cc_plan *p, const StepScalars &s, int32_t *flag, hi
 template <int BLK>
 void launch_lamb_phase1(const cc_plan *p, const StepScalars &s, int32_t *flag, hipStream_t st)
 {
+    if (p->grad_f32) launch_lamb_phase1_r<BLK, true>(p, s, flag, st);
+    else launch_lamb_phase1_r<BLK, false>(p, s, flag, st);
+}
+
+template <int BLK, bool GF32>
+void launch_reduce_r(const cc_plan *p, const StepScalars &s, int32_t *flag, hipStream_t st)
+{
     const dim3 grid((unsigned)p->chunks), block(BLK);
     switch (p->R) {
-#define CASE(r) case r: hipLaunchKernelGGL((lamb_phase1_kernel<r, BLK>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, p->d_partials, p->d_flag_scratch, flag); break;
+#define CASE(r) case r: hipLaunchKernelGGL((reduce_kernel<r, BLK, GF32>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, p->d_flag_scratch, flag); break;
         FOR_EACH_R(CASE)
 #undef CASE
     }
@@ -338,12 +371,8 @@ void launch_lamb_phase1(const cc_plan *p, const StepScalars &s, int32_t *flag, h
 template <int BLK>
 void launch_reduce(const cc_plan *p, const StepScalars &s, int32_t *flag, hipStream_t st)
 {
-    const dim3 grid((unsigned)p->chunks), block(BLK);
-    switch (p->R) {
-#define CASE(r) case r: hipLaunchKernelGGL((reduce_kernel<r, BLK>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, p->d_flag_scratch, flag); break;
-        FOR_EACH_R(CASE)
-#undef CASE
-    }
+    if (p->grad_f32) launch_reduce_r<BLK, true>(p, s, flag, st);
+    else launch_reduce_r<BLK, false>(p, s, flag, st);
 }
 
 template <int BLK>

@@ -37,7 +37,7 @@ struct DevTensor {
     const float *w_in, *m_in, *v_in;
     float *w_out, *m_out, *v_out;
     uint16_t *w16;
-    const uint16_t *grad[CC_MAX_R];
+    const void *grad[CC_MAX_R];   // fp16 bit patterns, or fp32 values when the plan says so
     float *gsum;              // unfused pipelines only: fp32 reduced gradient of this tensor
     float wd;
     uint32_t first_chunk;     // position of this tensor's first chunk in the table
@@ -224,40 +224,75 @@ __device__ __forceinline__ void stream_chunk(Op &op, uint32_t len)
     }
 }
 
-// Sum of the R slices for 4 elements, fixed rank order, fp32 (fp16 -> fp32 is exact, subnormals included).
-template <int R>
-__device__ __forceinline__ void reduce_grads(const f16x4 (&g)[R], float (&S)[4])
-{
-    S[0] = (float)g[0].x; S[1] = (float)g[0].y; S[2] = (float)g[0].z; S[3] = (float)g[0].w;
-#pragma unroll
-    for (int r = 1; r < R; ++r) {
-        S[0] += (float)g[r].x; S[1] += (float)g[r].y; S[2] += (float)g[r].z; S[3] += (float)g[r].w;
-    }
-}
+// The gradient source of a kernel: R slices reduced in registers in fixed rank order, fp32 accumulation.
+// The slices are fp16 (fp16 -> fp32 is exact, subnormals included; 8 bytes per lane and slice; fp32 running sum,
+// exact below |S| < 1 and within 6e-8 per add otherwise) or fp32 (16 bytes per lane and slice; see below).
+// The unfused pipelines read the fp32 sum that a reduce kernel stored instead (GradSum).
+template <int R, bool F32>
+struct GradSlices;
 
-// The gradient source of a kernel: R fp16 slices reduced in registers, or (unfused pipelines) the fp32 sum
-// that a reduce kernel stored.
 template <int R>
-struct GradSlices {
+struct GradSlices<R, false> {
     gcbytes g[R];
     struct Regs { f16x4 g[R]; };
     __device__ __forceinline__ void init(const DevTensor *t, uint64_t base)
     {
 #pragma unroll
-        for (int r = 0; r < R; ++r) g[r] = chunk_base((const void *)t->grad[r], base * 2);
+        for (int r = 0; r < R; ++r) g[r] = chunk_base(t->grad[r], base * 2);
     }
     __device__ __forceinline__ void load(Regs &x, uint32_t e) const
     {
 #pragma unroll
         for (int r = 0; r < R; ++r) x.g[r] = ld_f16x4(g[r], e * 2);
     }
-    __device__ __forceinline__ void sum(const Regs &x, float (&S)[4]) const { reduce_grads<R>(x.g, S); }
+    __device__ __forceinline__ void sum(const Regs &x, float (&S)[4]) const
+    {
+        S[0] = (float)x.g[0].x; S[1] = (float)x.g[0].y; S[2] = (float)x.g[0].z; S[3] = (float)x.g[0].w;
+#pragma unroll
+        for (int r = 1; r < R; ++r) {
+            S[0] += (float)x.g[r].x; S[1] += (float)x.g[r].y; S[2] += (float)x.g[r].z; S[3] += (float)x.g[r].w;
+        }
+    }
     __device__ __forceinline__ float sum1(uint32_t j) const
     {
         float S = ld_f16(g[0], j * 2);
 #pragma unroll
         for (int r = 1; r < R; ++r) S += ld_f16(g[r], j * 2);
         return S;
+    }
+};
+
+template <int R>
+struct GradSlices<R, true> {
+    gcbytes g[R];
+    struct Regs { f32x4 g[R]; };
+    __device__ __forceinline__ void init(const DevTensor *t, uint64_t base)
+    {
+#pragma unroll
+        for (int r = 0; r < R; ++r) g[r] = chunk_base(t->grad[r], base * 4);
+    }
+    __device__ __forceinline__ void load(Regs &x, uint32_t e) const
+    {
+#pragma unroll
+        for (int r = 0; r < R; ++r) x.g[r] = ld_f32x4(g[r], e * 4);
+    }
+    // fp32 slices are added in double and rounded to fp32 once: an fp32 running sum would carry up to
+    // (R-1) 2^-24 max|g| of rounding, which a near-zero sum turns into a large relative error of g^2 and, through
+    // elements with a small second moment, into an error of w above the 2e-6 bar.  16 fp64 operations per
+    // element stay far below the memory time.  A finite sum that does not fit fp32 becomes inf and raises the flag.
+    __device__ __forceinline__ void sum(const Regs &x, float (&S)[4]) const
+    {
+        double a = x.g[0].x, b = x.g[0].y, c = x.g[0].z, d = x.g[0].w;
+#pragma unroll
+        for (int r = 1; r < R; ++r) { a += (double)x.g[r].x; b += (double)x.g[r].y; c += (double)x.g[r].z; d += (double)x.g[r].w; }
+        S[0] = (float)a; S[1] = (float)b; S[2] = (float)c; S[3] = (float)d;
+    }
+    __device__ __forceinline__ float sum1(uint32_t j) const
+    {
+        double S = ld_f32(g[0], j * 4);
+#pragma unroll
+        for (int r = 1; r < R; ++r) S += (double)ld_f32(g[r], j * 4);
+        return (float)S;
     }
 };
 
@@ -330,13 +365,13 @@ struct AdamOp {
     }
 };
 
-template <int R, int MODE, int BLOCK, int GROUPS = 2>
+template <int R, int MODE, int BLOCK, bool GF32 = false, int GROUPS = 2>
 __global__ __launch_bounds__(BLOCK) void fused_adam_kernel(const DevTensor *__restrict__ tensors,
                                                            const Chunk *__restrict__ chunks, StepScalars s,
                                                            FlagScratch *__restrict__ fs, int32_t *__restrict__ flag)
 {
     const Where wh = locate(tensors, chunks, s.chunk_elems);
-    AdamOp<GradSlices<R>, MODE, true> op;
+    AdamOp<GradSlices<R, GF32>, MODE, true> op;
     op.init(wh.t, wh.base, s);
     stream_chunk<BLOCK, decltype(op), GROUPS>(op, wh.len);
     publish_flag<BLOCK>(op.bad, fs, flag);
@@ -459,13 +494,13 @@ __device__ __forceinline__ void lamb_phase1_body(const DevTensor *__restrict__ t
     if (RAISE) publish_flag<BLOCK>(op.bad, fs, flag);
 }
 
-template <int R, int BLOCK>
+template <int R, int BLOCK, bool GF32 = false>
 __global__ __launch_bounds__(BLOCK) void lamb_phase1_kernel(const DevTensor *__restrict__ tensors,
                                                             const Chunk *__restrict__ chunks, StepScalars s,
                                                             double *__restrict__ partials, FlagScratch *__restrict__ fs,
                                                             int32_t *__restrict__ flag)
 {
-    lamb_phase1_body<GradSlices<R>, true, BLOCK>(tensors, chunks, s, partials, fs, flag);
+    lamb_phase1_body<GradSlices<R, GF32>, true, BLOCK>(tensors, chunks, s, partials, fs, flag);
 }
 
 template <int BLOCK>
@@ -570,12 +605,12 @@ __global__ __launch_bounds__(BLOCK) void lamb_phase2_kernel(const DevTensor *__r
 // ---------------------------------------------------------------------------------------------------
 // Unfused pipeline pieces: reduce to an fp32 buffer, and the fp32 -> fp16 cast.
 // ---------------------------------------------------------------------------------------------------
-template <int R>
+template <int R, bool GF32>
 struct ReduceOp {
-    GradSlices<R> grad;
+    GradSlices<R, GF32> grad;
     gbytes gsum;
     bool bad = false;
-    struct Regs { typename GradSlices<R>::Regs g; float S[4]; };
+    struct Regs { typename GradSlices<R, GF32>::Regs g; float S[4]; };
     __device__ __forceinline__ void init(const DevTensor *t, uint64_t base)
     {
         grad.init(t, base);
@@ -596,13 +631,13 @@ struct ReduceOp {
     }
 };
 
-template <int R, int BLOCK>
+template <int R, int BLOCK, bool GF32 = false>
 __global__ __launch_bounds__(BLOCK) void reduce_kernel(const DevTensor *__restrict__ tensors,
                                                        const Chunk *__restrict__ chunks, StepScalars s,
                                                        FlagScratch *__restrict__ fs, int32_t *__restrict__ flag)
 {
     const Where wh = locate(tensors, chunks, s.chunk_elems);
-    ReduceOp<R> op;
+    ReduceOp<R, GF32> op;
     op.init(wh.t, wh.base);
     stream_chunk<BLOCK>(op, wh.len);
     publish_flag<BLOCK>(op.bad, fs, flag);

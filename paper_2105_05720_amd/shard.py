@@ -18,7 +18,8 @@ from .workloads import aligned_offsets
 
 class Shard:
     def __init__(self, numels: Sequence[int], weight_decays: Sequence[float], R: int, device="cuda",
-                 chunk_elems: int = 0, in_place: bool = False, align_elems: int = 4096, skew_elems: int = 0):
+                 chunk_elems: int = 0, in_place: bool = False, align_elems: int = 4096, skew_elems: int = 0,
+                 grad_dtype: torch.dtype = torch.float16):
         """align_elems: tensor starts are multiples of this many elements (>= 8 keeps them 16-byte aligned
         in the fp16 arenas).  The default places every tensor on a chunk boundary (4096 elements = 16 KiB of
         fp32), which measures ~5 % faster than 256-byte alignment: a chunk then covers whole DRAM interleave
@@ -39,7 +40,10 @@ class Shard:
         self.m = [f32() for _ in range(copies)]
         self.v = [f32() for _ in range(copies)]
         self.w16 = [torch.zeros(n, dtype=torch.float16, device=self.device) for _ in range(copies)]
-        self.grads = [torch.zeros(n, dtype=torch.float16, device=self.device) for _ in range(R)]
+        assert grad_dtype in (torch.float16, torch.float32)
+        self.grad_dtype = grad_dtype
+        gsize = 2 if grad_dtype == torch.float16 else 4
+        self.grads = [torch.zeros(n, dtype=grad_dtype, device=self.device) for _ in range(R)]
         self.flag = torch.zeros(1, dtype=torch.int32, device=self.device)
         self.cur = 0
         self.plans: List[cc.Plan] = []
@@ -51,10 +55,11 @@ class Shard:
                               w_out=self._addr(self.w[dst], k, 4), m_out=self._addr(self.m[dst], k, 4),
                               v_out=self._addr(self.v[dst], k, 4),
                               w16_out=self._addr(self.w16[dst], k, 2),
-                              grad=[self._addr(g, k, 2) for g in self.grads],
+                              grad=[self._addr(g, k, gsize) for g in self.grads],
                               weight_decay=self.wds[k])
                     for k, nk in enumerate(self.numels)]
-            self.plans.append(cc.cc_plan_create(tens, R, chunk_elems))
+            self.plans.append(cc.cc_plan_create_ex(tens, R, chunk_elems,
+                                                   cc.CC_GRAD_F16 if grad_dtype == torch.float16 else cc.CC_GRAD_F32))
 
     def _addr(self, arena: torch.Tensor, k: int, itemsize: int) -> int:
         return arena.data_ptr() + (self.skew + self.offsets[k]) * itemsize

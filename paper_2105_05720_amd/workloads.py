@@ -174,6 +174,7 @@ def grad_slice(numel: int, std: float, cfg_seed: int, step: int, rank: int, tens
         out = torch.empty(numel, dtype=torch.float16, device=device)
     if numel == 0:
         return out
+    # (an fp32 `out` keeps the drawn values unrounded: the Float 32 variant of the workload)
     g32 = torch.empty(numel, dtype=torch.float32, device=out.device)
     g32.normal_(0.0, std, generator=_gen(out.device, seed_key(cfg_seed, step, rank, tensor_index)))
     out.copy_(g32)          # round to nearest even, subnormals kept

@@ -27,6 +27,11 @@ def to_np_bits(t: torch.Tensor) -> np.ndarray:
     return t.detach().cpu().view(torch.int16).numpy().view(np.uint16).copy()
 
 
+def grad_to_np(shard: Shard, t: torch.Tensor) -> np.ndarray:
+    """A gradient slice as the oracle takes it: uint16 bit patterns for fp16 slices, float32 for fp32 slices."""
+    return to_np_bits(t) if shard.grad_dtype == torch.float16 else to_np_f32(t)
+
+
 def hyper_pair(**kw):
     """The same step scalars for both sides (two separate dataclasses; neither package imports the other)."""
     return cc.Hyper(**kw), oracle.Hyper(**kw)
@@ -44,7 +49,7 @@ class OracleState:
 
     def tensors(self, shard: Shard) -> List[oracle.OracleTensor]:
         return [oracle.OracleTensor(w=self.w[k], m=self.m[k], v=self.v[k],
-                                    grads=[to_np_bits(shard.grad_of(r, k)) for r in range(shard.R)],
+                                    grads=[grad_to_np(shard, shard.grad_of(r, k)) for r in range(shard.R)],
                                     weight_decay=shard.wds[k]) for k in self.which]
 
     def adopt(self, ots: List[oracle.OracleTensor]):

@@ -17,7 +17,8 @@ import oracle
 from paper_2105_05720_amd import binding as cc
 from paper_2105_05720_amd import workloads as W
 from paper_2105_05720_amd.shard import Shard
-from parity import THREADS, OracleState, all_inputs_finite, compare_committed, hyper_pair, run_steps, to_np_bits, to_np_f32
+from parity import (THREADS, OracleState, all_inputs_finite, compare_committed, grad_to_np, hyper_pair, run_steps, to_np_bits,
+                    to_np_f32)
 from util import half_ulp_distance, state_error
 
 pytestmark = pytest.mark.gpu
@@ -50,7 +51,7 @@ class SampledOracle:
 
     def step(self, shard, cfg, ohp):
         ots = [oracle.OracleTensor(w=self.w[k], m=self.m[k], v=self.v[k],
-                                   grads=[to_np_bits(shard.grad_of(r, k)[ix]) for r in range(cfg.R)],
+                                   grads=[grad_to_np(shard, shard.grad_of(r, k)[ix]) for r in range(cfg.R)],
                                    weight_decay=shard.wds[k]) for k, ix in enumerate(self.idx)]
         flag = oracle.adam_step(ots, ohp, threads=THREADS)
         self.w = [t.w_out for t in ots]
@@ -178,4 +179,19 @@ def test_config4_adam_gpt2_xl_overflow_skip():
             samp.compare(shard, "config 4 call %d sample" % call)
         compare_committed(shard, ost, "config 4 call %d whole tensors" % call)
     print("config 4: %d sampled elements per step" % samp.count)
+    shard.destroy()
+
+
+def test_config2_list_with_fp32_gradient_slices_sampled():
+    """The Float 32 variant of the workload (paper, Section 6.1.1): same list, the R slices kept in fp32."""
+    cfg = W.config(2)
+    shard = shard_for(cfg, grad_dtype=torch.float32)
+    samp = SampledOracle(shard, cfg, stride=97)
+    for t in (1, 2):
+        ghp, ohp = hp_of(cfg, t)
+        W.fill_grads(shard, cfg, t)
+        assert samp.step(shard, cfg, ohp) == 0
+        assert shard.step(cc.cc_fused_adam_step, ghp) == 0
+        torch.cuda.synchronize()
+        samp.compare(shard, "config 2 fp32 slices step %d" % t)
     shard.destroy()

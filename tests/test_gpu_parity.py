@@ -24,8 +24,8 @@ def wds_for(numels, wd=0.01):
     return [wd if (i % 3) else 0.0 for i in range(len(numels))]
 
 
-def adam_case(numels, R, steps=2, chunk=0, in_place=False, seed=1, gstd=1e-2, label="", **hkw):
-    shard = Shard(numels, wds_for(numels), R, chunk_elems=chunk, in_place=in_place, align_elems=8)
+def adam_case(numels, R, steps=2, chunk=0, in_place=False, seed=1, gstd=1e-2, label="", grad_dtype=torch.float16, **hkw):
+    shard = Shard(numels, wds_for(numels), R, chunk_elems=chunk, in_place=in_place, align_elems=8, grad_dtype=grad_dtype)
     seeded_state(shard, seed)
     ost = OracleState(shard, range(len(numels)))
     hps = [hyper_pair(step=t, **hkw) for t in range(1, steps + 1)]
@@ -35,8 +35,8 @@ def adam_case(numels, R, steps=2, chunk=0, in_place=False, seed=1, gstd=1e-2, la
     return rep
 
 
-def lamb_case(numels, R, steps=2, chunk=0, seed=1, gstd=1e-2, label="", gpu_fn=None, **hkw):
-    shard = Shard(numels, wds_for(numels), R, chunk_elems=chunk, align_elems=8)
+def lamb_case(numels, R, steps=2, chunk=0, seed=1, gstd=1e-2, label="", gpu_fn=None, grad_dtype=torch.float16, **hkw):
+    shard = Shard(numels, wds_for(numels), R, chunk_elems=chunk, align_elems=8, grad_dtype=grad_dtype)
     seeded_state(shard, seed)
     ost = OracleState(shard, range(len(numels)))
     hps = [hyper_pair(step=t, **hkw) for t in range(1, steps + 1)]
@@ -339,3 +339,57 @@ def test_state_copied_out_and_back_continues_identically():
         shard.destroy()
         return out
     assert _same(run(False), run(True))
+
+
+# ---------------------------------------------------------------------------- fp32 gradient slices
+
+@pytest.mark.parametrize("R", [1, 3, 8, 16])
+def test_fp32_gradients_adam(R):
+    adam_case(TINY + [20481], R, steps=2, grad_dtype=torch.float32, label="adam fp32 grads R=%d" % R)
+    adam_case(ODD_LIST, R, steps=2, chunk=4096, grad_dtype=torch.float32, loss_scale=128.0, label="adam fp32 grads big chunk R=%d" % R)
+
+
+@pytest.mark.parametrize("fn,ofn", [(cc.cc_fused_lamb_step, oracle.lamb_step), (cc.cc_unfused_lamb_step, oracle.lamb_step)])
+def test_fp32_gradients_lamb(fn, ofn):
+    lamb_case(ODD_LIST + [50000], 4, steps=2, grad_dtype=torch.float32, gpu_fn=fn, label="lamb fp32 grads")
+
+
+def test_fp32_gradients_fused_equals_unfused_and_modes():
+    def run(fn):
+        numels = [5000, 4096, 12289, 3]
+        shard = Shard(numels, [0.01] * 4, 8, align_elems=8, grad_dtype=torch.float32)
+        seeded_state(shard, 17)
+        for t in (1, 2):
+            seeded_grads(shard, 170 + t, 1e-2)
+            assert shard.step(fn, cc.Hyper(step=t, adam_mode=0, grad_average=1)) == 0
+        torch.cuda.synchronize()
+        out = (shard.w[shard.cur].cpu(), shard.m[shard.cur].cpu(), shard.v[shard.cur].cpu(),
+               shard.w16[shard.cur].view(torch.int16).cpu())
+        shard.destroy()
+        return out
+    assert _same(run(cc.cc_fused_adam_step), run(cc.cc_unfused_adam_step))
+    adam_case([4097, 65], 3, steps=2, grad_dtype=torch.float32, adam_mode=0, grad_average=1, label="adam fp32 grads L2 avg")
+    adam_case([4097, 65], 3, steps=2, grad_dtype=torch.float32, in_place=True, skip_mode=1, label="adam fp32 grads in place")
+
+
+def test_fp32_gradients_overflow_cases():
+    """inf and NaN inputs, and two finite slices whose fp32 sum overflows: all raise the flag and skip the step."""
+    numels = [6000, 100]
+    for case in ("inf", "nan", "finite overflow"):
+        shard = Shard(numels, [0.01, 0.0], 2, align_elems=8, grad_dtype=torch.float32)
+        seeded_state(shard, 18)
+        ost = OracleState(shard, range(2))
+
+        def fill(i):
+            seeded_grads(shard, 180 + i, 1e-2)
+            if i == 1:
+                if case == "inf":
+                    shard.grad_of(1, 0)[4099] = float("-inf")
+                elif case == "nan":
+                    shard.grad_of(0, 1)[99] = float("nan")
+                else:
+                    shard.grad_of(0, 0)[17] = 3e38
+                    shard.grad_of(1, 0)[17] = 3e38
+        hps = [hyper_pair(step=1), hyper_pair(step=2), hyper_pair(step=2)]
+        run_steps(shard, ost, cc.cc_fused_adam_step, oracle.adam_step, hps, "adam fp32 " + case, fill, expect_flags=[0, 1, 0])
+        shard.destroy()
