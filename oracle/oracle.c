@@ -52,12 +52,12 @@ double oracle_half_to_double(uint16_t h)
     return sign ? -mag : mag;
 }
 
-/* Nearest binary16 to x, ties to even; overflow goes to infinity. */
-uint16_t oracle_float_to_half(float x)
+/* Nearest binary16 to x, ties to even; overflow goes to infinity.  One rounding, straight from the double. */
+uint16_t oracle_double_to_half(double x)
 {
     const uint16_t sign = signbit(x) ? 0x8000u : 0u;
     if (isnan(x)) return (uint16_t)(sign | 0x7e00u);
-    const double a = fabs((double)x);
+    const double a = fabs(x);
     if (a >= 65520.0) return (uint16_t)(sign | 0x7c00u);  /* 65520 is the midpoint above the largest half; the tie goes to the even side, which is infinity */
     if (a < ldexp(1.0, -14)) {
         /* subnormal grid: multiples of 2^-24; 1024 steps lands exactly on the smallest normal */
@@ -71,6 +71,8 @@ uint16_t oracle_float_to_half(float x)
     if (mant == 2048.0) { mant = 1024.0; e += 1; }
     return (uint16_t)(sign | (uint16_t)((e + 15) << 10) | (uint16_t)((int)mant - 1024));
 }
+
+uint16_t oracle_float_to_half(float x) { return oracle_double_to_half((double)x); }
 
 /* ---- the reduced gradient of one element ---- */
 

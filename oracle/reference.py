@@ -19,17 +19,18 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "oracle.c")
+_SRCS = [_SRC, os.path.join(_HERE, "epilogue.c")]
 _LIB = os.path.join(_HERE, "liboracle.so")
 _lib = None
 
 
 def build(force: bool = False) -> str:
     """Compile oracle.c into liboracle.so next to it (plain C, -O2, no fast-math)."""
-    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    stale = (not os.path.exists(_LIB)) or any(os.path.getmtime(_LIB) < os.path.getmtime(f) for f in _SRCS)
     if force or stale:
         tmp = _LIB + ".tmp%d" % os.getpid()
         subprocess.check_call(["gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-fPIC", "-shared",
-                               "-o", tmp, _SRC, "-lm"])
+                               "-o", tmp] + _SRCS + ["-lm"])
         os.replace(tmp, _LIB)
     return _LIB
 
@@ -60,6 +61,17 @@ def _load():
         lib.oracle_adam_tensor.argtypes = common + [C.c_int, C.c_int]
         lib.oracle_lamb_tensor.restype = None
         lib.oracle_lamb_tensor.argtypes = common + [C.POINTER(C.c_double)]
+        lib.oracle_philox4x32_10.restype = None
+        lib.oracle_philox4x32_10.argtypes = [C.POINTER(C.c_uint32), C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)]
+        lib.oracle_dropout_word.restype = C.c_uint32
+        lib.oracle_dropout_word.argtypes = [C.c_uint64, C.c_uint64]
+        lib.oracle_dropout_threshold.restype = C.c_uint32
+        lib.oracle_dropout_threshold.argtypes = [C.c_float]
+        lib.oracle_double_to_half.restype = C.c_uint16
+        lib.oracle_double_to_half.argtypes = [C.c_double]
+        lib.oracle_mp_epilogue.restype = None
+        lib.oracle_mp_epilogue.argtypes = [C.c_uint64, C.c_uint64, C.c_uint32, C.c_int, _u16pp, _u16p, _u16p, _u16p,
+                                           C.c_float, C.c_uint64, C.POINTER(C.c_uint8)]
         _lib = lib
     return _lib
 
@@ -195,3 +207,39 @@ def lamb_step(tensors: List[OracleTensor], hp: Hyper, threads: int = 1) -> int:
         t.norms = (norms[0], norms[1])
     _map(one, tensors, threads)
     return flag
+
+
+# ---- model-parallel epilogue (oracle/epilogue.c) ----
+
+def philox4x32_10(ctr: Sequence[int], key: Sequence[int]) -> Tuple[int, int, int, int]:
+    c = (C.c_uint32 * 4)(*ctr)
+    k = (C.c_uint32 * 2)(*key)
+    out = (C.c_uint32 * 4)()
+    _load().oracle_philox4x32_10(c, k, out)
+    return tuple(out)
+
+
+def dropout_word(seed: int, index: int) -> int:
+    return _load().oracle_dropout_word(seed, index)
+
+
+def dropout_threshold(p: float) -> int:
+    return _load().oracle_dropout_threshold(p)
+
+
+def double_to_half(x: float) -> int:
+    return _load().oracle_double_to_half(x)
+
+
+def mp_epilogue(partials: Sequence[np.ndarray], bias: np.ndarray, residual: np.ndarray, first: int, p: float, seed: int):
+    """out = Dropout(sum of the R partial outputs + bias, p) + residual on one slice; returns (out bits, kept mask)."""
+    n = residual.size
+    arr = (_u16p * len(partials))()
+    for r, x in enumerate(partials):
+        assert x.dtype == np.uint16 and x.flags.c_contiguous and x.size == n
+        arr[r] = x.ctypes.data_as(_u16p)
+    out = np.empty(n, np.uint16)
+    kept = np.empty(n, np.uint8)
+    _load().oracle_mp_epilogue(n, first, bias.size, len(partials), arr, _u16(bias), _u16(residual), _u16(out),
+                               p, seed, kept.ctypes.data_as(C.POINTER(C.c_uint8)))
+    return out, kept

@@ -9,6 +9,8 @@ import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SRC = os.path.join(ROOT, "oracle", "oracle.c")
+SRC_EPILOGUE = os.path.join(ROOT, "oracle", "epilogue.c")
+PIN_FILES = [os.path.join(ROOT, "tests", "test_oracle_pins.py"), os.path.join(ROOT, "tests", "test_oracle_epilogue.py")]
 
 # (name, text in oracle.c, replacement, which occurrence)
 MUTANTS = [
@@ -41,6 +43,24 @@ MUTANTS = [
 ]
 
 
+# planted in epilogue.c
+EPILOGUE_MUTANTS = [
+    ("philox multiplier", "0xD2511F53u", "0xD2511F55u", 0),
+    ("philox key increment", "0x9E3779B9u", "0x9E3779B1u", 0),
+    ("philox nine rounds", "round < 10", "round < 9", 0),
+    ("philox lanes swapped", "n1 = lo1, n2 = hi0 ^ c[3] ^ k[1], n3 = lo0", "n1 = lo0, n2 = hi0 ^ c[3] ^ k[1], n3 = lo1", 0),
+    ("wrong word of the block", "return w[index % 4];", "return w[(index + 1) % 4];", 0),
+    ("block of two", "const uint64_t block = index / 4;", "const uint64_t block = index / 2;", 0),
+    ("seed high half ignored", "(uint32_t)(seed >> 32)};", "0u};", 0),
+    ("mask inverted", ">= threshold;", "< threshold;", 0),
+    ("scale is 1-p", "1.0 / (1.0 - (double)p_f)", "(1.0 - (double)p_f)", 0),
+    ("bias indexed by slice position", "bias[gi % hidden]", "bias[i % hidden]", 0),
+    ("mask indexed by slice position", "oracle_dropout_word(seed, gi)", "oracle_dropout_word(seed, i)", 0),
+    ("residual dropped too", "d + oracle_half_to_double(residual[i])", "keep ? d + oracle_half_to_double(residual[i]) : 0.0", 0),
+    ("only one rank", "for (int r = 0; r < R; ++r) sum +=", "for (int r = 0; r < 1; ++r) sum +=", 0),
+]
+
+
 def _replace_nth(text, old, new, nth):
     pos = -1
     for _ in range(nth + 1):
@@ -51,32 +71,33 @@ def _replace_nth(text, old, new, nth):
 
 def _pins_fail_against(path_so):
     env = dict(os.environ, ORACLE_SO=path_so)
-    r = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", "test_oracle_pins.py"),
-                        "-x", "-q", "-p", "no:cacheprovider"], cwd=ROOT, env=env,
+    r = subprocess.run([sys.executable, "-m", "pytest"] + PIN_FILES + ["-x", "-q", "-p", "no:cacheprovider"], cwd=ROOT, env=env,
                        stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     return r.returncode != 0, r.stdout[-400:]
 
 
 def test_every_planted_mistake_is_caught(tmp_path):
-    src = open(SRC).read()
+    src = {SRC: open(SRC).read(), SRC_EPILOGUE: open(SRC_EPILOGUE).read()}
+    cases = [(SRC, m) for m in MUTANTS] + [(SRC_EPILOGUE, m) for m in EPILOGUE_MUTANTS]
 
     def run(case):
-        i, (name, old, new, nth) = case
+        i, (which, (name, old, new, nth)) = case
         c = tmp_path / ("mut%d.c" % i)
         so = tmp_path / ("mut%d.so" % i)
-        c.write_text(_replace_nth(src, old, new, nth))
-        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-w", "-o", str(so), str(c), "-lm"])
+        c.write_text(_replace_nth(src[which], old, new, nth))
+        other = SRC_EPILOGUE if which == SRC else SRC
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-w", "-o", str(so), str(c), other, "-lm"])
         failed, tail = _pins_fail_against(str(so))
         return name, failed, tail
 
     with ThreadPoolExecutor(max_workers=4) as ex:
-        results = list(ex.map(run, enumerate(MUTANTS)))
+        results = list(ex.map(run, enumerate(cases)))
     missed = [name for name, failed, _ in results if not failed]
     assert not missed, "pins did not catch: %s" % missed
 
 
 def test_unmodified_copy_passes(tmp_path):
     so = tmp_path / "same.so"
-    subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-w", "-o", str(so), SRC, "-lm"])
+    subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-w", "-o", str(so), SRC, SRC_EPILOGUE, "-lm"])
     failed, tail = _pins_fail_against(str(so))
     assert not failed, tail
