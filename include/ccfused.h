@@ -170,6 +170,38 @@ int cc_lamb_norms_read(cc_plan *plan, double *h_sums, void *hip_stream);
 int cc_unfused_adam_step(cc_plan *plan, const cc_hparams *hp, int32_t *d_overflow_flag, void *hip_stream);
 int cc_unfused_lamb_step(cc_plan *plan, const cc_hparams *hp, int32_t *d_overflow_flag, void *hip_stream);
 
+/* ---- model-parallel epilogue (the paper's running example) ---- */
+
+/*
+ * Fig. 3: sum = AllReduce("+", layer); out = Dropout(sum + b, p) + r, all fp16, with the schedule of Fig. 5
+ * program 3 applied (reduce-scatter + pointwise work on the slice + all-gather fused, Section 3.3).  This is the
+ * compute side on ONE rank's slice of the flattened [B*S, H] tensor: element i of the slice is element first + i
+ * of the full tensor, its bias column is (first + i) % hidden.
+ *   out[i] = keep(first + i) ? (partial_0[i] + ... + partial_{R-1}[i] + bias[col]) / (1 - p) : 0,  plus residual[i]
+ * in fp32, rounded once to fp16.  keep() is Philox4x32-10 (counter = global index / 4, key = seed; the element
+ * takes word index % 4) >= floor(p 2^32): the mask depends only on (seed, global index), never on the slicing.
+ * Device pointers, 16-byte aligned; first and hidden must be multiples of 8; 0 <= p < 1; R in 1..CC_MAX_R.
+ */
+typedef struct cc_epilogue {
+    uint64_t        numel;                 /* elements of this rank's slice */
+    uint64_t        first;                 /* global index of its first element */
+    uint32_t        hidden;                /* H */
+    int32_t         R;                     /* number of partial outputs */
+    const uint16_t *partial[CC_MAX_R];     /* R fp16 partial outputs of the local MatMul, numel each */
+    const uint16_t *bias;                  /* hidden fp16 */
+    const uint16_t *residual;              /* numel fp16 */
+    uint16_t       *out;                   /* numel fp16 */
+    float           dropout_p;
+    uint64_t        seed;
+} cc_epilogue;
+
+/* One pass: 2R + 4 bytes per element. */
+int cc_fused_epilogue(const cc_epilogue *args, void *hip_stream);
+
+/* Reference pipeline with the same result: reduce the R partial outputs into `d_sum_scratch` (numel floats, device,
+ * 16-byte aligned, owned by the caller), then the pointwise kernel: 2R + 4 and 4 + 4 bytes per element. */
+int cc_unfused_epilogue(const cc_epilogue *args, float *d_sum_scratch, void *hip_stream);
+
 /* ---- measurement aid ---- */
 
 /* Plain streaming copy of `bytes` (multiple of 16, both pointers 16-byte aligned) device to device with

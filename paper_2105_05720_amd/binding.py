@@ -40,6 +40,12 @@ class cc_hparams(C.Structure):
                 ("adam_mode", C.c_int32), ("skip_mode", C.c_int32)]
 
 
+class cc_epilogue(C.Structure):
+    _fields_ = [("numel", C.c_uint64), ("first", C.c_uint64), ("hidden", C.c_uint32), ("R", C.c_int32),
+                ("partial", C.c_void_p * CC_MAX_R), ("bias", C.c_void_p), ("residual", C.c_void_p), ("out", C.c_void_p),
+                ("dropout_p", C.c_float), ("seed", C.c_uint64)]
+
+
 # every symbol include/ccfused.h declares
 EXPORTS = {
     "cc_chunk_count": (C.c_int64, [C.POINTER(C.c_uint64), C.c_int32, C.c_int32]),
@@ -57,6 +63,8 @@ EXPORTS = {
     "cc_lamb_norms_read": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.c_void_p]),
     "cc_unfused_adam_step": (C.c_int, [C.c_void_p, C.POINTER(cc_hparams), C.c_void_p, C.c_void_p]),
     "cc_unfused_lamb_step": (C.c_int, [C.c_void_p, C.POINTER(cc_hparams), C.c_void_p, C.c_void_p]),
+    "cc_fused_epilogue": (C.c_int, [C.POINTER(cc_epilogue), C.c_void_p]),
+    "cc_unfused_epilogue": (C.c_int, [C.POINTER(cc_epilogue), C.c_void_p, C.c_void_p]),
     "cc_copy_probe": (C.c_int, [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]),
     "cc_last_error": (C.c_char_p, []),
     "cc_version": (C.c_int, []),
@@ -251,6 +259,29 @@ def cc_lamb_norms_read(plan: Plan, T: int, stream=None):
     buf = (C.c_double * max(2 * T, 2))()
     _check(load().cc_lamb_norms_read(plan.handle, buf, _stream(stream)))
     return [(buf[2 * i], buf[2 * i + 1]) for i in range(T)]
+
+
+def _epilogue(partials, bias, residual, out, first: int, hidden: int, dropout_p: float, seed: int, numel=None) -> cc_epilogue:
+    e = cc_epilogue()
+    e.numel = residual.numel() if numel is None else numel
+    e.first, e.hidden, e.R = first, hidden, len(partials)
+    for r, x in enumerate(partials[:CC_MAX_R]):
+        e.partial[r] = _ptr(x)
+    e.bias, e.residual, e.out = _ptr(bias), _ptr(residual), _ptr(out)
+    e.dropout_p, e.seed = dropout_p, seed
+    return e
+
+
+def cc_fused_epilogue(partials, bias, residual, out, first: int, hidden: int, dropout_p: float, seed: int, stream=None,
+                      numel=None) -> None:
+    e = _epilogue(partials, bias, residual, out, first, hidden, dropout_p, seed, numel)
+    _check(load().cc_fused_epilogue(C.byref(e), _stream(stream)))
+
+
+def cc_unfused_epilogue(partials, bias, residual, out, sum_scratch, first: int, hidden: int, dropout_p: float, seed: int,
+                        stream=None, numel=None) -> None:
+    e = _epilogue(partials, bias, residual, out, first, hidden, dropout_p, seed, numel)
+    _check(load().cc_unfused_epilogue(C.byref(e), _ptr(sum_scratch), _stream(stream)))
 
 
 def cc_copy_probe(dst, src, nbytes: int, stream=None) -> None:

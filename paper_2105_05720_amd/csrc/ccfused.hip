@@ -511,6 +511,88 @@ int cc_unfused_lamb_step(cc_plan *p, const cc_hparams *hp, int32_t *flag, void *
     return cast_launch(p, s, flag, st, 1);
 }
 
+namespace {
+
+int check_epilogue(const cc_epilogue *e, EpilogueArgs *a)
+{
+    if (!e) return fail(CC_ERR_NULL, "epilogue arguments are NULL");
+    if (e->R < 1 || e->R > CC_MAX_R) return fail(CC_ERR_ARG, "epilogue: R = %d outside 1..%d", e->R, CC_MAX_R);
+    if (e->hidden == 0 || e->hidden % 8 != 0) return fail(CC_ERR_ARG, "epilogue: hidden = %u must be a positive multiple of 8", e->hidden);
+    if (e->first % 8 != 0) return fail(CC_ERR_ARG, "epilogue: first = %llu must be a multiple of 8", (unsigned long long)e->first);
+    if (!(e->dropout_p >= 0.f && e->dropout_p < 1.f)) return fail(CC_ERR_ARG, "epilogue: dropout_p = %g outside [0, 1)", (double)e->dropout_p);
+    if (e->numel > 0) {
+        const void *ptrs[3] = {e->bias, e->residual, e->out};
+        static const char *names[3] = {"bias", "residual", "out"};
+        for (int k = 0; k < 3; ++k) {
+            if (!ptrs[k]) return fail(CC_ERR_NULL, "epilogue: %s is NULL", names[k]);
+            if (misaligned(ptrs[k])) return fail(CC_ERR_ALIGN, "epilogue: %s is not 16-byte aligned", names[k]);
+        }
+        for (int r = 0; r < e->R; ++r) {
+            if (!e->partial[r]) return fail(CC_ERR_NULL, "epilogue: partial[%d] is NULL", r);
+            if (misaligned(e->partial[r])) return fail(CC_ERR_ALIGN, "epilogue: partial[%d] is not 16-byte aligned", r);
+        }
+    }
+    std::memset(a, 0, sizeof(*a));
+    a->numel = e->numel; a->first = e->first; a->hidden = e->hidden;
+    a->threshold = (uint32_t)std::floor((double)e->dropout_p * 4294967296.0);
+    a->key0 = (uint32_t)e->seed; a->key1 = (uint32_t)(e->seed >> 32);
+    a->scale = (float)(1.0 / (1.0 - (double)e->dropout_p));
+    for (int r = 0; r < e->R; ++r) a->partial[r] = e->partial[r];
+    a->bias = e->bias; a->residual = e->residual; a->out = e->out;
+    return CC_OK;
+}
+
+constexpr int kEpilogueBlock = 512;
+
+int epilogue_grid(uint64_t numel, uint32_t chunk, unsigned *grid)
+{
+    const uint64_t g = (numel + chunk - 1) / chunk;
+    if (g > 0x7fffffffull) return fail(CC_ERR_ARG, "epilogue: too many elements for one launch");
+    *grid = (unsigned)g;
+    return CC_OK;
+}
+
+}  // namespace
+
+int cc_fused_epilogue(const cc_epilogue *e, void *stream)
+{
+    EpilogueArgs a;
+    int rc = check_epilogue(e, &a);
+    if (rc) return rc;
+    if (e->numel == 0) return CC_OK;
+    unsigned grid;
+    if ((rc = epilogue_grid(e->numel, kEpilogueBlock * 8 * 2, &grid))) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    switch (e->R) {
+#define CASE(r) case r: hipLaunchKernelGGL((fused_epilogue_kernel<r, kEpilogueBlock>), dim3(grid), dim3(kEpilogueBlock), 0, st, a); break;
+        FOR_EACH_R(CASE)
+#undef CASE
+    }
+    return launched("fused_epilogue_kernel");
+}
+
+int cc_unfused_epilogue(const cc_epilogue *e, float *d_sum, void *stream)
+{
+    EpilogueArgs a;
+    int rc = check_epilogue(e, &a);
+    if (rc) return rc;
+    if (e->numel == 0) return CC_OK;
+    if (!d_sum) return fail(CC_ERR_NULL, "epilogue: d_sum_scratch is NULL");
+    if (misaligned(d_sum)) return fail(CC_ERR_ALIGN, "epilogue: d_sum_scratch is not 16-byte aligned");
+    a.sum = d_sum;
+    unsigned grid;
+    if ((rc = epilogue_grid(e->numel, kEpilogueBlock * 4 * 2, &grid))) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    switch (e->R) {
+#define CASE(r) case r: hipLaunchKernelGGL((epilogue_reduce_kernel<r, kEpilogueBlock>), dim3(grid), dim3(kEpilogueBlock), 0, st, a); break;
+        FOR_EACH_R(CASE)
+#undef CASE
+    }
+    if ((rc = launched("epilogue_reduce_kernel"))) return rc;
+    hipLaunchKernelGGL((epilogue_pointwise_kernel<kEpilogueBlock>), dim3(grid), dim3(kEpilogueBlock), 0, st, a);
+    return launched("epilogue_pointwise_kernel");
+}
+
 int cc_copy_probe(void *dst, const void *src, uint64_t bytes, void *stream)
 {
     if (!dst || !src) return fail(CC_ERR_NULL, "cc_copy_probe: NULL pointer");

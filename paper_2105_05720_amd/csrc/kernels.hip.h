@@ -25,7 +25,7 @@
 
 namespace ccf {
 
-constexpr int kLanePack = 4;           // consecutive elements a lane owns per group
+constexpr uint32_t kStatePack = 4;     // consecutive elements a lane owns per group wherever an fp32 array is written
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
@@ -187,16 +187,18 @@ __global__ void clear_flag_kernel(int32_t *flag) { *flag = 0; }
 
 // ---- the streaming skeleton --------------------------------------------------------------------------------------
 // An Op describes one kernel's per-element work:
-//   struct Regs;                                   registers of one group (4 elements of this lane)
-//   void load(Regs&, uint32_t e) const;            vector loads of elements e .. e+3 of the chunk
+//   static constexpr uint32_t kPack;               consecutive elements a lane owns per group
+//   struct Regs;                                   registers of one group (kPack elements of this lane)
+//   void load(Regs&, uint32_t e) const;            vector loads of elements e .. e+kPack-1 of the chunk
 //   void compute(Regs&);                           arithmetic on the group
 //   void store(const Regs&, uint32_t e) const;     vector stores
 //   void single(uint32_t j);                       one element, scalar accesses (ragged end of a tensor)
-// A sweep is two groups BLOCK*4 elements apart.  A full sweep issues the loads of both groups, then computes
+// A sweep is two groups BLOCK*kPack elements apart.  A full sweep issues the loads of both groups, then computes
 // and stores; the ragged end of a chunk (only a tensor's last chunk has one) falls back group by group.
 template <int BLOCK, class Op, int GROUPS = 2>
 __device__ __forceinline__ void stream_chunk(Op &op, uint32_t len)
 {
+    constexpr uint32_t kLanePack = Op::kPack;      // consecutive elements a lane owns per group
     constexpr uint32_t kGroup = BLOCK * kLanePack;
     constexpr uint32_t kSweep = GROUPS * kGroup;
     const uint32_t lane_e = threadIdx.x * kLanePack;
@@ -311,6 +313,7 @@ struct GradSum {
 // ---------------------------------------------------------------------------------------------------
 template <class Grad, int MODE, bool EMIT16>
 struct AdamOp {
+    static constexpr uint32_t kPack = kStatePack;
     Grad grad;
     gcbytes w_in, m_in, v_in;
     gbytes w_out, m_out, v_out, w16;
@@ -425,6 +428,7 @@ __device__ __forceinline__ void block_sum2(double &a, double &b)
 // ---------------------------------------------------------------------------------------------------
 template <class Grad>
 struct LambPhase1Op {
+    static constexpr uint32_t kPack = kStatePack;
     Grad grad;
     gcbytes w_in, m_in, v_in;
     gbytes m_out, v_out;
@@ -546,6 +550,7 @@ __global__ __launch_bounds__(kNormBlock) void lamb_norms_kernel(const DevTensor 
 // unfused pipeline, where a separate cast kernel writes the fp16 copy.
 template <bool EMIT16>
 struct LambPhase2Op {
+    static constexpr uint32_t kPack = kStatePack;
     gcbytes w_in, m_new, v_new;
     gbytes w_out, w16;
     StepScalars s;
@@ -607,6 +612,7 @@ __global__ __launch_bounds__(BLOCK) void lamb_phase2_kernel(const DevTensor *__r
 // ---------------------------------------------------------------------------------------------------
 template <int R, bool GF32>
 struct ReduceOp {
+    static constexpr uint32_t kPack = kStatePack;
     GradSlices<R, GF32> grad;
     gbytes gsum;
     bool bad = false;
@@ -644,6 +650,7 @@ __global__ __launch_bounds__(BLOCK) void reduce_kernel(const DevTensor *__restri
 }
 
 struct CastOp {
+    static constexpr uint32_t kPack = kStatePack;
     gcbytes w_new;
     gbytes w16;
     struct Regs { float w[4]; };
@@ -669,6 +676,236 @@ __global__ __launch_bounds__(BLOCK) void cast_kernel(const DevTensor *__restrict
     CastOp op;
     op.init(wh.t, wh.base);
     stream_chunk<BLOCK>(op, wh.len);
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Model-parallel epilogue (Fig. 3 with the schedule of Fig. 5, program 3) on one rank's slice:
+//     out = Dropout(partial_0 + ... + partial_{R-1} + bias, p) + residual,  every tensor fp16.
+// All streams are fp16, so a lane owns 8 consecutive elements and every access is 16 bytes (1 KiB per wave
+// instruction).  2R + 4 bytes per element.  The dropout mask is a counter-based generator of the global element
+// index (Philox4x32 with 10 rounds: counter = index / 4, key = seed, word index % 4), so that it does not depend on
+// how the tensor is sliced or chunked; an element is kept iff its word >= floor(p 2^32).
+// ---------------------------------------------------------------------------------------------------
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+
+struct EpilogueArgs {
+    uint64_t numel;           // elements of this slice
+    uint64_t first;           // global index of the slice's first element (multiple of 8)
+    uint32_t hidden;          // H: the bias column of global element i is i % H (multiple of 8)
+    uint32_t threshold;       // floor(p 2^32)
+    uint32_t key0, key1;      // seed, low and high half
+    float scale;              // 1 / (1 - p)
+    const uint16_t *partial[CC_MAX_R];
+    const uint16_t *bias;
+    const uint16_t *residual;
+    uint16_t *out;
+    float *sum;               // unfused pipeline only: fp32 reduced partial outputs
+};
+
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0, uint32_t k1,
+                                              uint32_t (&out)[4])
+{
+#pragma unroll
+    for (int round = 0; round < 10; ++round) {
+        const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+        const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+        c0 = hi1 ^ c1 ^ k0;
+        c1 = lo1;
+        c2 = hi0 ^ c3 ^ k1;
+        c3 = lo0;
+        k0 += 0x9E3779B9u;      // the key schedule; the bump after the last round is unused
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+// The pointwise part for one element whose reduced sum is x_sum (fp32).
+__device__ __forceinline__ float epilogue_value(float x_sum, float bias, float residual, bool keep, float scale)
+{
+    const float x = x_sum + bias;
+    return (keep ? x * scale : 0.0f) + residual;
+}
+
+__device__ __forceinline__ f16x8 ld_f16x8(gcbytes b, uint32_t off) { return __builtin_nontemporal_load((const CCF_GLOBAL f16x8 *)(b + off)); }
+__device__ __forceinline__ void st_f16x8(gbytes b, uint32_t off, f16x8 x) { __builtin_nontemporal_store(x, (CCF_GLOBAL f16x8 *)(b + off)); }
+
+// Common part of the fused kernel and of the unfused pipeline's pointwise kernel: mask, bias column, output.
+struct EpilogueTail {
+    gcbytes res, bias;
+    gbytes out;
+    uint64_t gbase;           // global index of the chunk's first element
+    uint32_t col_base;        // bias column of the chunk's first element
+    uint32_t hidden, threshold, k0, k1;
+    float scale;
+    __device__ __forceinline__ void init(const EpilogueArgs &a, uint64_t base)
+    {
+        res = chunk_base((const void *)a.residual, base * 2);
+        bias = (gcbytes)a.bias;
+        out = chunk_base((void *)a.out, base * 2);
+        gbase = a.first + base;
+        col_base = (uint32_t)(gbase % a.hidden);
+        hidden = a.hidden; threshold = a.threshold; k0 = a.key0; k1 = a.key1; scale = a.scale;
+    }
+    // words of the Philox block that holds global elements 4q .. 4q+3, q = (gbase + e) / 4
+    __device__ __forceinline__ void words(uint32_t e, uint32_t (&w)[4]) const
+    {
+        const uint64_t block = (gbase + e) >> 2;
+        philox4x32_10((uint32_t)block, (uint32_t)(block >> 32), 0u, 0u, k0, k1, w);
+    }
+    __device__ __forceinline__ uint32_t column(uint32_t e) const { return (col_base + e) % hidden; }
+    __device__ __forceinline__ void single(uint32_t j, float x_sum) const
+    {
+        uint32_t w[4];
+        words(j, w);
+        const bool keep = w[(gbase + j) & 3] >= threshold;
+        st_f16(out, j * 2, epilogue_value(x_sum, ld_f16(bias, column(j) * 2), ld_f16(res, j * 2), keep, scale));
+    }
+};
+
+template <int R>
+struct FusedEpilogueOp {
+    static constexpr uint32_t kPack = 8;
+    gcbytes part[R];
+    EpilogueTail t;
+    struct Regs { f16x8 p[R]; f16x8 r; f16x8 b; uint32_t e; };
+    __device__ __forceinline__ void init(const EpilogueArgs &a, uint64_t base)
+    {
+#pragma unroll
+        for (int r = 0; r < R; ++r) part[r] = chunk_base((const void *)a.partial[r], base * 2);
+        t.init(a, base);
+    }
+    __device__ __forceinline__ void load(Regs &x, uint32_t e) const
+    {
+#pragma unroll
+        for (int r = 0; r < R; ++r) x.p[r] = ld_f16x8(part[r], e * 2);
+        x.r = ld_f16x8(t.res, e * 2);
+        x.b = *(const CCF_GLOBAL f16x8 *)(t.bias + t.column(e) * 2);     // 8 columns never wrap: H and e are multiples of 8
+        x.e = e;
+    }
+    __device__ __forceinline__ void compute(Regs &x)
+    {
+        uint32_t w[8];
+        uint32_t lo[4], hi[4];
+        t.words(x.e, lo);
+        t.words(x.e + 4, hi);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) { w[k] = lo[k]; w[4 + k] = hi[k]; }
+        f16x8 o;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            float sum = (float)x.p[0][k];
+#pragma unroll
+            for (int r = 1; r < R; ++r) sum += (float)x.p[r][k];
+            o[k] = to_half(epilogue_value(sum, (float)x.b[k], (float)x.r[k], w[k] >= t.threshold, t.scale));
+        }
+        x.r = o;
+    }
+    __device__ __forceinline__ void store(const Regs &x, uint32_t e) const { st_f16x8(t.out, e * 2, x.r); }
+    __device__ __forceinline__ void single(uint32_t j)
+    {
+        float sum = ld_f16(part[0], j * 2);
+#pragma unroll
+        for (int r = 1; r < R; ++r) sum += ld_f16(part[r], j * 2);
+        t.single(j, sum);
+    }
+};
+
+template <int R, int BLOCK>
+__global__ __launch_bounds__(BLOCK) void fused_epilogue_kernel(EpilogueArgs a)
+{
+    constexpr uint32_t kChunk = BLOCK * 8 * 2;
+    const uint64_t base = (uint64_t)blockIdx.x * kChunk;
+    const uint64_t rem = a.numel - base;
+    FusedEpilogueOp<R> op;
+    op.init(a, base);
+    stream_chunk<BLOCK>(op, rem < kChunk ? (uint32_t)rem : kChunk);
+}
+
+// Unfused pipeline: reduce the R partial outputs into an fp32 buffer (a lane owns 4 elements, so that the fp32
+// stores of a wave are contiguous), then the pointwise kernel on that buffer.
+template <int R>
+struct EpilogueReduceOp {
+    static constexpr uint32_t kPack = 4;
+    gcbytes part[R];
+    gbytes sum;
+    struct Regs { f16x4 p[R]; float S[4]; };
+    __device__ __forceinline__ void init(const EpilogueArgs &a, uint64_t base)
+    {
+#pragma unroll
+        for (int r = 0; r < R; ++r) part[r] = chunk_base((const void *)a.partial[r], base * 2);
+        sum = chunk_base((void *)a.sum, base * 4);
+    }
+    __device__ __forceinline__ void load(Regs &x, uint32_t e) const
+    {
+#pragma unroll
+        for (int r = 0; r < R; ++r) x.p[r] = ld_f16x4(part[r], e * 2);
+    }
+    __device__ __forceinline__ void compute(Regs &x)
+    {
+        x.S[0] = (float)x.p[0].x; x.S[1] = (float)x.p[0].y; x.S[2] = (float)x.p[0].z; x.S[3] = (float)x.p[0].w;
+#pragma unroll
+        for (int r = 1; r < R; ++r) { x.S[0] += (float)x.p[r].x; x.S[1] += (float)x.p[r].y; x.S[2] += (float)x.p[r].z; x.S[3] += (float)x.p[r].w; }
+    }
+    __device__ __forceinline__ void store(const Regs &x, uint32_t e) const { st_f32x4(sum, e * 4, x.S); }
+    __device__ __forceinline__ void single(uint32_t j)
+    {
+        float S = ld_f16(part[0], j * 2);
+#pragma unroll
+        for (int r = 1; r < R; ++r) S += ld_f16(part[r], j * 2);
+        st_f32(sum, j * 4, S);
+    }
+};
+
+struct EpiloguePointwiseOp {
+    static constexpr uint32_t kPack = 4;
+    gcbytes sum;
+    EpilogueTail t;
+    struct Regs { float S[4]; f16x4 r; f16x4 b; uint32_t e; };
+    __device__ __forceinline__ void init(const EpilogueArgs &a, uint64_t base)
+    {
+        sum = chunk_base((const void *)a.sum, base * 4);
+        t.init(a, base);
+    }
+    __device__ __forceinline__ void load(Regs &x, uint32_t e) const
+    {
+        ld_f32x4(sum, e * 4, x.S);
+        x.r = ld_f16x4(t.res, e * 2);
+        x.b = *(const CCF_GLOBAL f16x4 *)(t.bias + t.column(e) * 2);
+        x.e = e;
+    }
+    __device__ __forceinline__ void compute(Regs &x)
+    {
+        uint32_t w[4];
+        t.words(x.e, w);
+        const float b[4] = {(float)x.b.x, (float)x.b.y, (float)x.b.z, (float)x.b.w};
+        const float r[4] = {(float)x.r.x, (float)x.r.y, (float)x.r.z, (float)x.r.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) x.S[k] = epilogue_value(x.S[k], b[k], r[k], w[k] >= t.threshold, t.scale);
+    }
+    __device__ __forceinline__ void store(const Regs &x, uint32_t e) const { st_f16x4(t.out, e * 2, x.S); }
+    __device__ __forceinline__ void single(uint32_t j) { t.single(j, ld_f32(sum, j * 4)); }
+};
+
+template <int R, int BLOCK>
+__global__ __launch_bounds__(BLOCK) void epilogue_reduce_kernel(EpilogueArgs a)
+{
+    constexpr uint32_t kChunk = BLOCK * 4 * 2;
+    const uint64_t base = (uint64_t)blockIdx.x * kChunk;
+    const uint64_t rem = a.numel - base;
+    EpilogueReduceOp<R> op;
+    op.init(a, base);
+    stream_chunk<BLOCK>(op, rem < kChunk ? (uint32_t)rem : kChunk);
+}
+
+template <int BLOCK>
+__global__ __launch_bounds__(BLOCK) void epilogue_pointwise_kernel(EpilogueArgs a)
+{
+    constexpr uint32_t kChunk = BLOCK * 4 * 2;
+    const uint64_t base = (uint64_t)blockIdx.x * kChunk;
+    const uint64_t rem = a.numel - base;
+    EpiloguePointwiseOp op;
+    op.init(a, base);
+    stream_chunk<BLOCK>(op, rem < kChunk ? (uint32_t)rem : kChunk);
 }
 
 // Plain streaming copy, 16 bytes per lane, four accesses in flight per lane.

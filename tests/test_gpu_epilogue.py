@@ -1,0 +1,133 @@
+"""Parity of the fused model-parallel epilogue (paper, Fig. 3) with its CPU oracle, through the C ABI.
+
+Dropped elements must equal the residual bit for bit (the mask is an integer decision taken by the same
+counter-based generator on both sides).  Kept elements: the GPU evaluates (sum + b) s + r in fp32 (three roundings
+of 2^-24 relative to the larger addend) and rounds to fp16, the oracle rounds the fp64 value; they must agree
+within one fp16 ulp taken at the magnitude of the larger of |out| and |residual| (where the two addends cancel,
+an fp16 ulp of the small result is finer than fp32 arithmetic on the addends can resolve)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2105_05720_amd import binding as cc
+from parity import to_np_bits
+from util import bits_to_f64, half_ulp_distance
+
+pytestmark = pytest.mark.gpu
+
+
+def make(n, R, hidden, seed, scale=0.5):
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    partials = [torch.empty(n, device="cuda").normal_(0, scale, generator=g).half() for _ in range(R)]
+    bias = torch.empty(hidden, device="cuda").normal_(0, 0.1, generator=g).half()
+    residual = torch.empty(n, device="cuda").normal_(0, 1.0, generator=g).half()
+    return partials, bias, residual
+
+
+def check(out_bits, partials, bias, residual, first, p, seed, lo=0, hi=None):
+    """GPU output bits [lo, hi) of a slice against the oracle on the same range."""
+    hi = residual.numel() if hi is None else hi
+    want, kept = oracle.mp_epilogue([to_np_bits(x[lo:hi]) for x in partials], to_np_bits(bias), to_np_bits(residual[lo:hi]),
+                                    first + lo, p, seed)
+    got = out_bits[lo:hi]
+    dropped = kept == 0
+    assert np.array_equal(got[dropped], to_np_bits(residual[lo:hi])[dropped]), "a dropped element is not the residual"
+    d = half_ulp_distance(got, want)
+    assert d.size == 0 or np.mean(d == 0) > 0.98
+    gv, wv = bits_to_f64(got), bits_to_f64(want)
+    mag = np.maximum(np.abs(wv), np.abs(bits_to_f64(to_np_bits(residual[lo:hi]))))
+    with np.errstate(divide="ignore"):
+        ulp = np.where(mag >= 2.0 ** -14, 2.0 ** (np.floor(np.log2(np.maximum(mag, 2.0 ** -14))) - 10), 2.0 ** -24)
+    fin = np.isfinite(wv)
+    assert np.array_equal(np.isfinite(gv), fin)
+    assert np.all(np.abs(gv - wv)[fin] <= ulp[fin]), "kept elements differ by more than one fp16 ulp of the larger addend"
+    return kept
+
+
+@pytest.mark.parametrize("R", [1, 2, 8, 16])
+@pytest.mark.parametrize("n,hidden,first", [(8, 8, 0), (64, 96, 96 * 5), (8192, 3072, 3072 * 7 + 8), (8192 * 3 + 24, 1024, 8),
+                                            (100003, 96, 2 ** 33 + 16)])
+def test_fused_epilogue_matches_oracle(R, n, hidden, first):
+    for p, seed in ((0.0, 1), (0.1, 2 ** 40 + 3), (0.5, 7)):
+        partials, bias, residual = make(n, R, hidden, 1000 + R)
+        out = torch.zeros(n, dtype=torch.float16, device="cuda")
+        cc.cc_fused_epilogue(partials, bias, residual, out, first, hidden, p, seed)
+        torch.cuda.synchronize()
+        kept = check(to_np_bits(out), partials, bias, residual, first, p, seed)
+        if p == 0.0:
+            assert kept.all()
+
+
+@pytest.mark.parametrize("n", [8, 4097 * 8, 100003])
+def test_fused_equals_unfused_epilogue_bit_for_bit(n):
+    partials, bias, residual = make(n, 8, 96, 5)
+    a = torch.zeros(n, dtype=torch.float16, device="cuda")
+    b = torch.zeros(n, dtype=torch.float16, device="cuda")
+    scratch = torch.empty(n + 8, dtype=torch.float32, device="cuda")
+    cc.cc_fused_epilogue(partials, bias, residual, a, 960, 96, 0.1, 11)
+    cc.cc_unfused_epilogue(partials, bias, residual, b, scratch, 960, 96, 0.1, 11)
+    torch.cuda.synchronize()
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+    check(to_np_bits(b), partials, bias, residual, 960, 0.1, 11)
+
+
+def test_mask_does_not_depend_on_slicing():
+    n, H, p, seed = 8192 * 5, 128, 0.3, 21
+    partials, bias, residual = make(n, 4, H, 6)
+    whole = torch.zeros(n, dtype=torch.float16, device="cuda")
+    cc.cc_fused_epilogue(partials, bias, residual, whole, 0, H, p, seed)
+    cut = 8192 + 64
+    pieces = torch.zeros(n, dtype=torch.float16, device="cuda")
+    for a, b in ((0, cut), (cut, n)):
+        cc.cc_fused_epilogue([x[a:b] for x in partials], bias, residual[a:b], pieces[a:b], a, H, p, seed)
+    torch.cuda.synchronize()
+    assert torch.equal(whole.view(torch.int16), pieces.view(torch.int16))
+
+
+def test_epilogue_at_the_paper_size_sampled():
+    """[B, S, H] = [8, 1024, 3072] (the GPT-2 8.3B sizes of the paper's standalone experiment), R = 8, p = 0.1;
+    the oracle recomputes ranges at the start, in the middle (across chunk borders) and at the end."""
+    B, S, H, R, p, seed = 8, 1024, 3072, 8, float(np.float32(0.1)), 2021
+    n = B * S * H
+    partials, bias, residual = make(n, R, H, 9, scale=0.3)
+    out = torch.zeros(n, dtype=torch.float16, device="cuda")
+    cc.cc_fused_epilogue(partials, bias, residual, out, 0, H, p, seed)
+    torch.cuda.synchronize()
+    bits = to_np_bits(out)
+    kept_total = 0
+    for lo in (0, 8192 * 1000 - 4096, n // 2 + 8, n - 60000):
+        kept_total += check(bits, partials, bias, residual, 0, p, seed, lo, lo + 60000).sum()
+    assert abs(kept_total / 240000 - (1 - p)) < 0.005
+    # one rank's 1/8 slice gives the same values as the same range of the full tensor
+    a, b = n // 8 * 3, n // 8 * 4
+    piece = torch.zeros(b - a, dtype=torch.float16, device="cuda")
+    cc.cc_fused_epilogue([x[a:b] for x in partials], bias, residual[a:b], piece, a, H, p, seed)
+    torch.cuda.synchronize()
+    assert torch.equal(piece.view(torch.int16), out[a:b].view(torch.int16))
+
+
+def test_epilogue_argument_checks():
+    partials, bias, residual = make(64, 2, 8, 1)
+    out = torch.zeros(64, dtype=torch.float16, device="cuda")
+    out.fill_(3.0)
+    bad = [dict(hidden=12), dict(hidden=0), dict(first=4), dict(dropout_p=1.0), dict(dropout_p=-0.1), dict(dropout_p=float("nan"))]
+    for kw in bad:
+        args = dict(first=0, hidden=8, dropout_p=0.1, seed=1)
+        args.update(kw)
+        with pytest.raises(cc.CcError) as e:
+            cc.cc_fused_epilogue(partials, bias, residual, out, **args)
+        assert e.value.code == cc.CC_ERR_ARG
+    with pytest.raises(cc.CcError) as e:
+        cc.cc_fused_epilogue(partials, None, residual, out, 0, 8, 0.1, 1)
+    assert e.value.code == cc.CC_ERR_NULL
+    with pytest.raises(cc.CcError) as e:
+        cc.cc_fused_epilogue([partials[0], partials[1][1:]], bias, residual, out, 0, 8, 0.1, 1, numel=56)
+    assert e.value.code == cc.CC_ERR_ALIGN
+    with pytest.raises(cc.CcError) as e:
+        cc.cc_unfused_epilogue(partials, bias, residual, out, None, 0, 8, 0.1, 1)
+    assert e.value.code == cc.CC_ERR_NULL
+    torch.cuda.synchronize()
+    assert float(out.min()) == 3.0 and float(out.max()) == 3.0           # nothing ran
+    cc.cc_fused_epilogue(partials, bias, residual, out, 0, 8, 0.1, 1, numel=0)    # an empty slice is legal
