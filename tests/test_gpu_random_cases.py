@@ -1,0 +1,67 @@
+"""Seeded random sweep over list shapes, R, modes, hyper-parameters, gradient type, chunk size and pipeline:
+every case is compared with the oracle element by element (same bar as the hand-picked cases)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2105_05720_amd import binding as cc
+from paper_2105_05720_amd.shard import Shard
+from parity import OracleState, hyper_pair, run_steps, seeded_grads, seeded_state
+
+pytestmark = pytest.mark.gpu
+
+
+def draw_case(rng):
+    T = int(rng.integers(1, 9))
+    kinds = rng.integers(0, 5, T)
+    numels = []
+    for k in kinds:
+        if k == 0:
+            numels.append(int(rng.integers(0, 9)))                       # empty and tiny
+        elif k == 1:
+            numels.append(int(rng.integers(9, 1100)))
+        elif k == 2:
+            numels.append(int(rng.choice([1024, 2048, 4096, 8192, 12288])))  # exact multiples
+        elif k == 3:
+            numels.append(int(rng.integers(1100, 30000)))
+        else:
+            numels.append(int(rng.integers(30000, 90000)))
+    if sum(numels) == 0:
+        numels[0] = 17
+    lamb = bool(rng.integers(0, 2))
+    case = dict(numels=numels, R=int(rng.integers(1, 17)), lamb=lamb,
+                chunk=int(rng.choice([0, 1024, 2048, 4096, 8192])),
+                unfused=bool(rng.integers(0, 2)), f32=bool(rng.integers(0, 3) == 0),
+                gstd=float(rng.choice([3e-5, 1e-3, 1e-2, 0.3])),
+                wds=[float(rng.choice([0.0, 0.01, 0.1])) for _ in numels],
+                hp=dict(lr=float(rng.choice([1e-4, 1e-3, 2e-2])), beta1=float(rng.choice([0.0, 0.5, 0.9, 0.95])),
+                        beta2=float(rng.choice([0.9, 0.98, 0.999])), eps=float(rng.choice([1e-8, 1e-6, 1e-3])),
+                        loss_scale=float(rng.choice([1.0, 128.0, 65536.0, 3.0, 1000.0])),
+                        grad_average=int(rng.integers(0, 2))))
+    if not lamb:
+        case["hp"]["adam_mode"] = int(rng.integers(0, 2))
+        case["in_place"] = bool(rng.integers(0, 3) == 0)
+        case["hp"]["skip_mode"] = 1 if case["in_place"] else int(rng.integers(0, 2))
+    else:
+        case["in_place"] = False
+    return case
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_case(seed):
+    rng = np.random.default_rng(1000 + seed)
+    c = draw_case(rng)
+    shard = Shard(c["numels"], c["wds"], c["R"], chunk_elems=c["chunk"], in_place=c["in_place"], align_elems=8,
+                  grad_dtype=torch.float32 if c["f32"] else torch.float16)
+    seeded_state(shard, seed)
+    ost = OracleState(shard, range(len(c["numels"])))
+    if c["lamb"]:
+        gpu_fn, ofn = (cc.cc_unfused_lamb_step if c["unfused"] else cc.cc_fused_lamb_step), oracle.lamb_step
+    else:
+        gpu_fn, ofn = (cc.cc_unfused_adam_step if c["unfused"] else cc.cc_fused_adam_step), oracle.adam_step
+    t0 = int(rng.integers(1, 2000))
+    hps = [hyper_pair(step=t0 + i, **c["hp"]) for i in range(2)]
+    run_steps(shard, ost, gpu_fn, ofn, hps, "random case %d %r" % (seed, c),
+              lambda i: seeded_grads(shard, seed * 10 + i, c["gstd"] * c["hp"]["loss_scale"] if c["hp"]["loss_scale"] <= 128 else c["gstd"]))
+    shard.destroy()
