@@ -24,8 +24,8 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 
 # HBM bytes per launch of the headline kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by what
-# the same counter reads for the plain copy kernel (profiles/fused_adam_config2.md): default chunk size only.
-MEASURED_TRAFFIC_BYTES = {2: 9.4256e9 + 4.7069e9}
+# the same counter reads for the plain copy kernel: default chunk size, fp16 slices, scattered list only.
+MEASURED_TRAFFIC_BYTES = {2: 9.4258e9 + 4.7096e9, 3: 1.3473e10 + 4.7122e9}     # profiles/fused_adam_config2.md, fused_lamb_config3.md
 
 
 GRAD_BYTES = 2                 # bytes per gradient element (set to 4 by --grad-dtype f32)
@@ -246,6 +246,11 @@ def main() -> int:
         torch.cuda.synchronize()
         extras["copy_kernel_GB/s"] = round(2 * nbytes / (e0.elapsed_time(e1) / 20 * 1e-3) / 1e9, 1)
         del src, dst
+        cus, clk_khz, bus_bits, total_bytes = cc.cc_device_info()
+        extras["device"] = {"name": torch.cuda.get_device_name(0), "compute_units": cus, "memory_clock_khz": clk_khz,
+                            "memory_bus_bits": bus_bits, "total_GiB": round(total_bytes / 2 ** 30, 1),
+                            # double data rate: 2 transfers per clock on every bus bit
+                            "GB/s_from_device_props": round(2 * clk_khz * 1e3 * bus_bits / 8 / 1e9, 1)}
         out["extras"] = extras
 
         out["cpu_baseline"] = cpu_baseline(shard, cfg, hyper(1), args.cpu_seconds)
@@ -299,8 +304,14 @@ def cpu_baseline(shard, cfg, ghp, target_seconds):
     t0 = time.perf_counter()
     step_fn(ots, ohp, threads=threads)
     dt = time.perf_counter() - t0
+    # the definition itself: one thread, on the calibration tensors
+    ots1 = tensors_of(calib)
+    t0 = time.perf_counter()
+    step_fn(ots1, ohp, threads=1)
+    single = sum(cfg.params[k].numel for k in calib) / (time.perf_counter() - t0)
     bpp = adam_bytes_per_param(cfg.R) if cfg.optimizer == "adam" else lamb_bytes_per_param(cfg.R)
-    return {"value": round(bpp * total / dt / 1e9, 4), "unit": "GB/s", "params_per_sec": round(total / dt, 1),
+    return {"single_thread_params_per_sec": round(single, 1),
+            "value": round(bpp * total / dt / 1e9, 4), "unit": "GB/s", "params_per_sec": round(total / dt, 1),
             "cores": threads, "kind": "oracle", "seconds": round(dt, 2),
             "sample": "%d of the %d tensors of the same list (%d params), one %s step, whole tensors spread over %d threads" % (
                 len(sample), len(cfg.params), total, cfg.optimizer, threads)}

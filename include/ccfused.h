@@ -208,6 +208,10 @@ int cc_unfused_epilogue(const cc_epilogue *args, float *d_sum_scratch, void *hip
  * the same launch shape as the fused kernels; gives the practical HBM ceiling and calibrates counters. */
 int cc_copy_probe(void *d_dst, const void *d_src, uint64_t bytes, void *hip_stream);
 
+/* What the current device reports about itself (any output pointer may be NULL): compute units, memory clock in
+ * kHz and memory bus width in bits as hipDeviceGetAttribute gives them, total device memory in bytes. */
+int cc_device_info(int32_t *compute_units, int32_t *memory_clock_khz, int32_t *memory_bus_bits, uint64_t *total_bytes);
+
 const char *cc_last_error(void);
 int cc_version(void);
 

@@ -66,6 +66,7 @@ EXPORTS = {
     "cc_fused_epilogue": (C.c_int, [C.POINTER(cc_epilogue), C.c_void_p]),
     "cc_unfused_epilogue": (C.c_int, [C.POINTER(cc_epilogue), C.c_void_p, C.c_void_p]),
     "cc_copy_probe": (C.c_int, [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]),
+    "cc_device_info": (C.c_int, [C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_uint64)]),
     "cc_last_error": (C.c_char_p, []),
     "cc_version": (C.c_int, []),
 }
@@ -286,6 +287,13 @@ def cc_unfused_epilogue(partials, bias, residual, out, sum_scratch, first: int, 
 
 def cc_copy_probe(dst, src, nbytes: int, stream=None) -> None:
     _check(load().cc_copy_probe(_ptr(dst), _ptr(src), nbytes, _stream(stream)))
+
+
+def cc_device_info():
+    """(compute units, memory clock kHz, memory bus bits, total bytes) of the current device."""
+    cus, clk, bus, tot = C.c_int32(), C.c_int32(), C.c_int32(), C.c_uint64()
+    _check(load().cc_device_info(C.byref(cus), C.byref(clk), C.byref(bus), C.byref(tot)))
+    return cus.value, clk.value, bus.value, tot.value
 
 
 def cc_last_error() -> str:

@@ -593,6 +593,21 @@ int cc_unfused_epilogue(const cc_epilogue *e, float *d_sum, void *stream)
     return launched("epilogue_pointwise_kernel");
 }
 
+int cc_device_info(int32_t *cus, int32_t *clock_khz, int32_t *bus_bits, uint64_t *total_bytes)
+{
+    int dev = 0, v = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    if (cus) { HIP_TRY(hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev)); *cus = v; }
+    if (clock_khz) { HIP_TRY(hipDeviceGetAttribute(&v, hipDeviceAttributeMemoryClockRate, dev)); *clock_khz = v; }
+    if (bus_bits) { HIP_TRY(hipDeviceGetAttribute(&v, hipDeviceAttributeMemoryBusWidth, dev)); *bus_bits = v; }
+    if (total_bytes) {
+        size_t free_b = 0, total_b = 0;
+        HIP_TRY(hipMemGetInfo(&free_b, &total_b));
+        *total_bytes = (uint64_t)total_b;
+    }
+    return CC_OK;
+}
+
 int cc_copy_probe(void *dst, const void *src, uint64_t bytes, void *stream)
 {
     if (!dst || !src) return fail(CC_ERR_NULL, "cc_copy_probe: NULL pointer");

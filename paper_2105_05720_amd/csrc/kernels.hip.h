@@ -165,6 +165,15 @@ __device__ __forceinline__ void publish_flag(bool bad, FlagScratch *fs, int32_t 
 {
     const int any = BLOCK > 64 ? __syncthreads_or(bad ? 1 : 0) : (__builtin_amdgcn_ballot_w64(bad) != 0ull ? 1 : 0);
     if (threadIdx.x == 0) {
+        const unsigned long long mine0 = 1ull | (any ? (1ull << 32) : 0ull);
+        if (gridDim.x <= kFlagSlots) {                  // few workgroups: count on the top word directly
+            const unsigned long long tprev = atomicAdd(&fs->top.word, mine0);
+            if ((uint32_t)tprev == gridDim.x - 1) {
+                *flag = ((tprev + mine0) >> 32) != 0ull ? 1 : 0;
+                atomicExch(&fs->top.word, 0ull);
+            }
+            return;
+        }
         const uint32_t slot = blockIdx.x % kFlagSlots;
         const uint32_t in_slot = (gridDim.x - slot + kFlagSlots - 1) / kFlagSlots;      // workgroups b with b % 64 == slot
         const uint32_t slots_used = gridDim.x < kFlagSlots ? gridDim.x : kFlagSlots;

@@ -425,3 +425,36 @@ def test_fp32_gradient_overflow_is_decided_on_the_fp32_sum():
     t = make_tensor(w, over)
     assert oracle.adam_step([t], Hyper(step=1)) == 1
     assert np.array_equal(t.w_out, w)
+
+
+# ----------------------------------------------------------------------------- brute force on tiny tensors
+
+def test_tiny_tensors_against_a_numpy_float64_loop():
+    """A second, independent write-up of the per-element program in numpy float64, element by element.  (It
+    restates the formula, so it guards the C code against slips rather than pinning the formula itself.)"""
+    rng = np.random.default_rng(40)
+    for n, R in ((1, 1), (2, 3), (7, 8), (9, 16)):
+        w, m, v, grads = _random_case(rng, n, R)
+        hp = Hyper(lr=3e-3, beta1=0.8, beta2=0.99, eps=1e-7, loss_scale=8.0, step=5, grad_average=1)
+        wd = 0.05
+        ot = make_tensor(w, grads, m, v, wd)
+        lt = make_tensor(w, grads, m, v, wd)
+        oracle.adam_step([ot], hp)
+        oracle.lamb_step([lt], hp)
+        lr, b1, b2, eps, wdf = F(hp.lr), F(hp.beta1), F(hp.beta2), F(hp.eps), F(wd)
+        us, ws = [], []
+        for i in range(n):
+            S = 0.0
+            for g in grads:
+                S += float(bits_to_f64(g[i:i + 1])[0])
+            gh = S / (8.0 * R)
+            mi = b1 * float(m[i]) + (1 - b1) * gh
+            vi = b2 * float(v[i]) + (1 - b2) * gh * gh
+            u = (mi / (1 - b1 ** 5)) / (np.sqrt(vi / (1 - b2 ** 5)) + eps) + wdf * float(w[i])
+            us.append(u)
+            ws.append(float(w[i]))
+            assert ot.m_out[i] == np.float32(mi) and ot.v_out[i] == np.float32(vi)
+            assert ulp_f32(ot.w_out[i:i + 1], np.array([np.float32(ws[-1] - lr * u)])).max() <= 1
+        ratio = np.linalg.norm(ws) / np.linalg.norm(us)
+        for i in range(n):
+            assert ulp_f32(lt.w_out[i:i + 1], np.array([np.float32(ws[i] - lr * ratio * us[i])])).max() <= 1
