@@ -249,8 +249,9 @@ def main() -> int:
         cus, clk_khz, bus_bits, total_bytes = cc.cc_device_info()
         extras["device"] = {"name": torch.cuda.get_device_name(0), "compute_units": cus, "memory_clock_khz": clk_khz,
                             "memory_bus_bits": bus_bits, "total_GiB": round(total_bytes / 2 ** 30, 1),
-                            # double data rate: 2 transfers per clock on every bus bit
-                            "GB/s_from_device_props": round(2 * clk_khz * 1e3 * bus_bits / 8 / 1e9, 1)}
+                            # HBM3E moves 4 bits per pin per reported (command) clock: 2 GHz -> 8 Gb/s per pin;
+                            # 8192 pins x 8 Gb/s / 8 = 8192 GB/s, the published 8 TB/s
+                            "GB/s_at_4_transfers_per_clock": round(4 * clk_khz * 1e3 * bus_bits / 8 / 1e9, 1)}
         out["extras"] = extras
 
         out["cpu_baseline"] = cpu_baseline(shard, cfg, hyper(1), args.cpu_seconds)
