@@ -76,13 +76,18 @@ uint16_t oracle_float_to_half(float x) { return oracle_double_to_half((double)x)
 
 /* ---- the reduced gradient of one element ---- */
 
-/* The R slices hold fp16 bit patterns (mixed precision, the paper's main case) or, with grad_f32, fp32 values
- * (Section 6.1.1 reports Float 32 as qualitatively similar). */
+uint16_t oracle_float_to_half(float x);
+
+/* The R slices hold fp16 bit patterns (mixed precision, the paper's main case) or, with grad_f32 == 1, fp32 values
+ * (Section 6.1.1 reports Float 32 as qualitatively similar).  grad_f32 == 2 is the unfused baseline as a framework
+ * runs it (Section 6.1.1, the AR-Opt schedule over an fp16 all-reduce): fp16 slices whose sum comes back from the
+ * reduction as an fp16 tensor, i.e. the fp32 sum rounded to fp16 before the optimizer sees it. */
 static double reduced_sum(const void *const *g, int grad_f32, int R, uint64_t i)
 {
     double S = 0.0;
     for (int r = 0; r < R; ++r)                                        /* the "+" all-reduce of Fig. 4a */
-        S += grad_f32 ? (double)((const float *)g[r])[i] : oracle_half_to_double(((const uint16_t *)g[r])[i]);
+        S += grad_f32 == 1 ? (double)((const float *)g[r])[i] : oracle_half_to_double(((const uint16_t *)g[r])[i]);
+    if (grad_f32 == 2) S = oracle_half_to_double(oracle_float_to_half((float)S));
     return S;
 }
 

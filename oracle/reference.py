@@ -142,10 +142,10 @@ def float_to_half(x: float) -> int:
     return _load().oracle_float_to_half(float(np.float32(x)))
 
 
-def grad_overflow(grads: Sequence[np.ndarray]) -> int:
+def grad_overflow(grads: Sequence[np.ndarray], sum_f16: bool = False) -> int:
     n = grads[0].size
     ptrs, f32 = _gptrs(grads, n)
-    return int(_load().oracle_grad_overflow(n, len(grads), ptrs, f32))
+    return int(_load().oracle_grad_overflow(n, len(grads), ptrs, 2 if (sum_f16 and not f32) else f32))
 
 
 def _map(fn, tensors, threads):
@@ -160,15 +160,16 @@ def _keep(t: OracleTensor):
                                _f32(t.w_out), _f32(t.m_out), _f32(t.v_out), _u16(t.w16_out))
 
 
-def adam_step(tensors: List[OracleTensor], hp: Hyper, threads: int = 1) -> int:
+def adam_step(tensors: List[OracleTensor], hp: Hyper, threads: int = 1, sum_f16: bool = False) -> int:
     """One Adam step over every tensor of the slice; fills *_out, returns the overflow flag.
 
     threads > 1 only spreads whole tensors over host threads; each tensor is still one sequential loop.
+    sum_f16: the reduced gradient passes through fp16 before the optimizer (the unfused fp16 all-reduce baseline).
     """
     lib = _load()
     for t in tensors:
         _alloc_outputs(t)
-    flag = int(any(_map(lambda t: grad_overflow(t.grads) if t.w.size else 0, tensors, threads)))
+    flag = int(any(_map(lambda t: grad_overflow(t.grads, sum_f16) if t.w.size else 0, tensors, threads)))
     if flag and hp.skip_mode == 0:
         _map(_keep, tensors, threads)
         return flag
@@ -176,6 +177,9 @@ def adam_step(tensors: List[OracleTensor], hp: Hyper, threads: int = 1) -> int:
     def one(t: OracleTensor):
         n = t.w.size
         ptrs, f32 = _gptrs(t.grads, n)
+        if sum_f16:
+            assert not f32, "the fp16 intermediate is defined for fp16 slices"
+            f32 = 2
         lib.oracle_adam_tensor(n, len(t.grads), ptrs, f32, _f32(t.w), _f32(t.m), _f32(t.v),
                                _f32(t.w_out), _f32(t.m_out), _f32(t.v_out), _u16(t.w16_out),
                                hp.lr, hp.beta1, hp.beta2, hp.eps, t.weight_decay, hp.loss_scale,

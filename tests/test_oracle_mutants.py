@@ -21,8 +21,9 @@ MUTANTS = [
     ("update sign", "const double p_ = wi - lr * u;", "const double p_ = wi + lr * u;", 0),
     ("decoupled decay dropped", "if (adam_mode != 0) u += wd * wi;", "", 0),
     ("L2 decay dropped", "if (adam_mode == 0) gh += wd * wi;", "", 0),
-    ("only the last rank is kept", "S += grad_f32 ?", "S = grad_f32 ?", 0),
-    ("fp32 slices read as halves", "grad_f32 ? (double)((const float *)g[r])[i]", "0 ? (double)((const float *)g[r])[i]", 0),
+    ("only the last rank is kept", "S += grad_f32 == 1 ?", "S = grad_f32 == 1 ?", 0),
+    ("fp32 slices read as halves", "grad_f32 == 1 ? (double)((const float *)g[r])[i]", "0 ? (double)((const float *)g[r])[i]", 0),
+    ("fp16 intermediate not rounded", "if (grad_f32 == 2) S = oracle_half_to_double(oracle_float_to_half((float)S));", "", 0),
     ("flag decided in double", "return !isfinite((float)S);", "return !isfinite(S);", 0),
     ("step off by one", "pow(beta1, (double)step)", "pow(beta1, (double)(step + 1))", 0),
     ("gradient not squared", "(double)v[i] * beta2 + (1.0 - beta2) * gh * gh;\n        const double m1", "(double)v[i] * beta2 + (1.0 - beta2) * gh;\n        const double m1", 0),

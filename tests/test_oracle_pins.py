@@ -458,3 +458,27 @@ def test_tiny_tensors_against_a_numpy_float64_loop():
         ratio = np.linalg.norm(ws) / np.linalg.norm(us)
         for i in range(n):
             assert ulp_f32(lt.w_out[i:i + 1], np.array([np.float32(ws[i] - lr * ratio * us[i])])).max() <= 1
+
+
+# ----------------------------------------------------------------------------- fp16 intermediate (unfused baseline)
+
+def test_fp16_intermediate_equals_one_rank_with_the_rounded_sum():
+    """With sum_f16 the optimizer must see exactly fp16(fp32(sum)): the same as a single slice holding that value."""
+    rng = np.random.default_rng(50)
+    n, R = 4000, 8
+    w, m, v, grads = _random_case(rng, n, R, gstd=0.7)                   # |S| > 1: the rounding to fp16 matters
+    hp = Hyper(step=3, loss_scale=2.0)
+    a = make_tensor(w, grads, m, v, 0.01)
+    assert oracle.adam_step([a], hp, sum_f16=True) == 0
+    S = sum(bits_to_f64(g) for g in grads)
+    with np.errstate(over="ignore"):
+        S16 = S.astype(np.float32).astype(np.float16)                     # numpy: fp32 then fp16, nearest even
+    b = make_tensor(w, [S16.view(np.uint16)], m, v, 0.01)
+    oracle.adam_step([b], hp)
+    assert np.array_equal(a.w_out, b.w_out) and np.array_equal(a.m_out, b.m_out) and np.array_equal(a.v_out, b.v_out)
+    c = make_tensor(w, grads, m, v, 0.01)
+    oracle.adam_step([c], hp)
+    assert not np.array_equal(a.m_out, c.m_out)                            # and it differs from the exact-sum path
+    # a finite sum beyond the fp16 range comes back as inf and raises the flag
+    big = [half_bits(np.full(8, 60000.0)), half_bits(np.full(8, 60000.0))]
+    assert oracle.grad_overflow(big) == 0 and oracle.grad_overflow(big, sum_f16=True) == 1
