@@ -210,6 +210,9 @@ def main() -> int:
         else:
             extras["fused_adam_same_list"] = rate(cc.cc_fused_adam_step, adam_bytes_per_param(R), ks)
         extras["unfused_adam"] = rate(cc.cc_unfused_adam_step, unfused_adam_bytes_per_param(R), ks)
+        if args.grad_dtype == "f16":          # reduce 2R + 2, optimizer 14 + 12, cast 4 + 2
+            extras["unfused_adam_fp16_intermediate"] = rate(
+                lambda p, h, f, st=None: cc.cc_unfused_adam_step_ex(p, h, f, st, cc.CC_GRAD_F16), 2 * R + 34, ks)
         if not args.in_place:
             extras["unfused_lamb"] = rate(cc.cc_unfused_lamb_step, unfused_lamb_bytes_per_param(R), ks)
         fa = extras.get("fused_adam_same_list", {"ms_per_step": ms})["ms_per_step"] if cfg.optimizer != "adam" else ms

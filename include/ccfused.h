@@ -170,6 +170,15 @@ int cc_lamb_norms_read(cc_plan *plan, double *h_sums, void *hip_stream);
 int cc_unfused_adam_step(cc_plan *plan, const cc_hparams *hp, int32_t *d_overflow_flag, void *hip_stream);
 int cc_unfused_lamb_step(cc_plan *plan, const cc_hparams *hp, int32_t *d_overflow_flag, void *hip_stream);
 
+/*
+ * The unfused Adam pipeline with the element type of the intermediate stated.  CC_GRAD_F32 is cc_unfused_adam_step.
+ * CC_GRAD_F16 is the baseline as a framework runs it over an fp16 all-reduce (Section 6.1.1, AR-Opt): the reduce
+ * kernel hands fp16(fp32(sum)) to the optimizer kernel, which changes the numerics (the fused kernel keeps the
+ * sum in fp32 registers for free) and raises the flag when a finite sum leaves the fp16 range.  fp16 slices only.
+ */
+int cc_unfused_adam_step_ex(cc_plan *plan, const cc_hparams *hp, int32_t *d_overflow_flag, void *hip_stream,
+                            int32_t sum_dtype);
+
 /* ---- model-parallel epilogue (the paper's running example) ---- */
 
 /*

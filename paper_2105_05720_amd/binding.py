@@ -62,6 +62,7 @@ EXPORTS = {
     "cc_lamb_norm_buffer": (C.c_int, [C.c_void_p, C.POINTER(C.c_void_p)]),
     "cc_lamb_norms_read": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.c_void_p]),
     "cc_unfused_adam_step": (C.c_int, [C.c_void_p, C.POINTER(cc_hparams), C.c_void_p, C.c_void_p]),
+    "cc_unfused_adam_step_ex": (C.c_int, [C.c_void_p, C.POINTER(cc_hparams), C.c_void_p, C.c_void_p, C.c_int32]),
     "cc_unfused_lamb_step": (C.c_int, [C.c_void_p, C.POINTER(cc_hparams), C.c_void_p, C.c_void_p]),
     "cc_fused_epilogue": (C.c_int, [C.POINTER(cc_epilogue), C.c_void_p]),
     "cc_unfused_epilogue": (C.c_int, [C.POINTER(cc_epilogue), C.c_void_p, C.c_void_p]),
@@ -243,6 +244,11 @@ def cc_fused_lamb_phase2(plan: Plan, hp, flag, stream=None) -> None:
 
 def cc_unfused_adam_step(plan: Plan, hp, flag, stream=None) -> None:
     _step("cc_unfused_adam_step", plan, hp, flag, stream)
+
+
+def cc_unfused_adam_step_ex(plan: Plan, hp, flag, stream=None, sum_dtype: int = CC_GRAD_F32) -> None:
+    c = _hp(hp)
+    _check(load().cc_unfused_adam_step_ex(plan.handle, C.byref(c), _ptr(flag), _stream(stream), sum_dtype))
 
 
 def cc_unfused_lamb_step(plan: Plan, hp, flag, stream=None) -> None:

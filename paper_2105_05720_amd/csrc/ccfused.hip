@@ -375,15 +375,26 @@ void launch_reduce(const cc_plan *p, const StepScalars &s, int32_t *flag, hipStr
     else launch_reduce_r<BLK, false>(p, s, flag, st);
 }
 
-template <int BLK>
+template <int BLK, bool SUM16>
 void launch_adam_from_sum(const cc_plan *p, const StepScalars &s, const int32_t *flag, hipStream_t st, int mode)
 {
     const dim3 grid((unsigned)p->chunks), block(BLK);
     switch (mode) {
-        case 0: hipLaunchKernelGGL((adam_from_sum_kernel<0, BLK>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag); break;
-        case 1: hipLaunchKernelGGL((adam_from_sum_kernel<1, BLK>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag); break;
-        case 2: hipLaunchKernelGGL((adam_from_sum_kernel<2, BLK>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag); break;
-        default: hipLaunchKernelGGL((adam_from_sum_kernel<3, BLK>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag); break;
+        case 0: hipLaunchKernelGGL((adam_from_sum_kernel<0, BLK, SUM16>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag); break;
+        case 1: hipLaunchKernelGGL((adam_from_sum_kernel<1, BLK, SUM16>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag); break;
+        case 2: hipLaunchKernelGGL((adam_from_sum_kernel<2, BLK, SUM16>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag); break;
+        default: hipLaunchKernelGGL((adam_from_sum_kernel<3, BLK, SUM16>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag); break;
+    }
+}
+
+template <int BLK>
+void launch_reduce_half(const cc_plan *p, const StepScalars &s, int32_t *flag, hipStream_t st)
+{
+    const dim3 grid((unsigned)p->chunks), block(BLK);
+    switch (p->R) {
+#define CASE(r) case r: hipLaunchKernelGGL((reduce_half_kernel<r, BLK>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, p->d_flag_scratch, flag); break;
+        FOR_EACH_R(CASE)
+#undef CASE
     }
 }
 
@@ -476,16 +487,26 @@ int cc_fused_lamb_step(cc_plan *p, const cc_hparams *hp, int32_t *flag, void *st
 
 int cc_unfused_adam_step(cc_plan *p, const cc_hparams *hp, int32_t *flag, void *stream)
 {
+    return cc_unfused_adam_step_ex(p, hp, flag, stream, CC_GRAD_F32);
+}
+
+int cc_unfused_adam_step_ex(cc_plan *p, const cc_hparams *hp, int32_t *flag, void *stream, int32_t sum_dtype)
+{
     StepScalars s;
     int rc = check_step(p, hp, flag, Opt::Adam, &s);
     if (rc) return rc;
+    if (sum_dtype != CC_GRAD_F32 && sum_dtype != CC_GRAD_F16) return fail(CC_ERR_ARG, "sum_dtype = %d", sum_dtype);
+    const bool sum16 = sum_dtype == CC_GRAD_F16;
+    if (sum16 && p->grad_f32) return fail(CC_ERR_ARG, "an fp16 intermediate needs fp16 gradient slices");
     if ((rc = ensure_gsum(p))) return rc;
     hipStream_t st = (hipStream_t)stream;
     if (p->chunks == 0) return clear_flag(flag, st);
-    BY_BLOCK(p, launch_reduce<BLK>(p, s, flag, st));
+    if (sum16) BY_BLOCK(p, launch_reduce_half<BLK>(p, s, flag, st));
+    else BY_BLOCK(p, launch_reduce<BLK>(p, s, flag, st));
     if ((rc = launched("reduce_kernel"))) return rc;
     const int mode = (hp->skip_mode == 1 ? kModeGuard : 0) | (hp->adam_mode == 0 ? kModeL2 : 0);
-    BY_BLOCK(p, launch_adam_from_sum<BLK>(p, s, flag, st, mode));
+    if (sum16) BY_BLOCK(p, (launch_adam_from_sum<BLK, true>(p, s, flag, st, mode)));
+    else BY_BLOCK(p, (launch_adam_from_sum<BLK, false>(p, s, flag, st, mode)));
     if ((rc = launched("adam_from_sum_kernel"))) return rc;
     return cast_launch(p, s, flag, st, hp->skip_mode == 0 ? 1 : 0);
 }

@@ -21,6 +21,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "ccfused.h"
 
 namespace ccf {
@@ -316,6 +318,16 @@ struct GradSum {
     __device__ __forceinline__ float sum1(uint32_t j) const { return ld_f32(s, j * 4); }
 };
 
+// The reduced sum as an fp16 all-reduce hands it over: fp16 values in the first half of the tensor's sum buffer.
+struct GradSumHalf {
+    gcbytes s;
+    struct Regs { f16x4 s; };
+    __device__ __forceinline__ void init(const DevTensor *t, uint64_t base) { s = chunk_base((const void *)t->gsum, base * 2); }
+    __device__ __forceinline__ void load(Regs &x, uint32_t e) const { x.s = ld_f16x4(s, e * 2); }
+    __device__ __forceinline__ void sum(const Regs &x, float (&S)[4]) const { S[0] = (float)x.s.x; S[1] = (float)x.s.y; S[2] = (float)x.s.z; S[3] = (float)x.s.w; }
+    __device__ __forceinline__ float sum1(uint32_t j) const { return ld_f16(s, j * 2); }
+};
+
 // ---------------------------------------------------------------------------------------------------
 // Adam: reduce (or read the reduced sum) + moments + weight update (+ fp16 emission when fused).
 // One pass, 2R + 26 bytes per parameter when fused.
@@ -392,14 +404,14 @@ __global__ __launch_bounds__(BLOCK) void fused_adam_kernel(const DevTensor *__re
 // Unfused pipeline, optimizer stage: the same update from the stored fp32 sum; the cast kernel emits fp16.
 // In whole-step-skip mode the flag is already final here (the reduce kernel set it), so an overflowed step
 // writes nothing.
-template <int MODE, int BLOCK>
+template <int MODE, int BLOCK, bool SUM16 = false>
 __global__ __launch_bounds__(BLOCK) void adam_from_sum_kernel(const DevTensor *__restrict__ tensors,
                                                               const Chunk *__restrict__ chunks, StepScalars s,
                                                               const int32_t *__restrict__ flag)
 {
     if (!(MODE & kModeGuard) && *flag != 0) return;
     const Where wh = locate(tensors, chunks, s.chunk_elems);
-    AdamOp<GradSum, MODE, false> op;
+    AdamOp<typename std::conditional<SUM16, GradSumHalf, GradSum>::type, MODE, false> op;
     op.init(wh.t, wh.base, s);
     stream_chunk<BLOCK>(op, wh.len);
 }
@@ -653,6 +665,60 @@ __global__ __launch_bounds__(BLOCK) void reduce_kernel(const DevTensor *__restri
 {
     const Where wh = locate(tensors, chunks, s.chunk_elems);
     ReduceOp<R, GF32> op;
+    op.init(wh.t, wh.base);
+    stream_chunk<BLOCK>(op, wh.len);
+    publish_flag<BLOCK>(op.bad, fs, flag);
+}
+
+// The reduce stage of the fp16 all-reduce baseline: the sum of the R fp16 slices leaves as fp16.  The slices are
+// added in double (exact for up to 16 fp16 values) and rounded to fp32, then to fp16, so that the stored value is
+// fp16(fp32(sum)) whatever the order of the additions.  The flag is decided on the fp16 value: a finite sum beyond
+// 65504 comes back as inf, as it would from an fp16 collective.
+template <int R>
+struct ReduceHalfOp {
+    static constexpr uint32_t kPack = kStatePack;
+    GradSlices<R, false> grad;
+    gbytes gsum;
+    bool bad = false;
+    struct Regs { typename GradSlices<R, false>::Regs g; float S[4]; };
+    __device__ __forceinline__ void init(const DevTensor *t, uint64_t base)
+    {
+        grad.init(t, base);
+        gsum = chunk_base((void *)t->gsum, base * 2);
+    }
+    __device__ __forceinline__ void load(Regs &x, uint32_t e) const { grad.load(x.g, e); }
+    static __device__ __forceinline__ float through_half(double s, bool &bad)
+    {
+        const float h = (float)to_half((float)s);
+        bad = bad || not_finite(h);
+        return h;
+    }
+    __device__ __forceinline__ void compute(Regs &x)
+    {
+        double a = (double)(float)x.g.g[0].x, b = (double)(float)x.g.g[0].y, c = (double)(float)x.g.g[0].z, d = (double)(float)x.g.g[0].w;
+#pragma unroll
+        for (int r = 1; r < R; ++r) {
+            a += (double)(float)x.g.g[r].x; b += (double)(float)x.g.g[r].y; c += (double)(float)x.g.g[r].z; d += (double)(float)x.g.g[r].w;
+        }
+        x.S[0] = through_half(a, bad); x.S[1] = through_half(b, bad); x.S[2] = through_half(c, bad); x.S[3] = through_half(d, bad);
+    }
+    __device__ __forceinline__ void store(const Regs &x, uint32_t e) const { st_f16x4(gsum, e * 2, x.S); }
+    __device__ __forceinline__ void single(uint32_t j)
+    {
+        double S = (double)ld_f16(grad.g[0], j * 2);
+#pragma unroll
+        for (int r = 1; r < R; ++r) S += (double)ld_f16(grad.g[r], j * 2);
+        st_f16(gsum, j * 2, through_half(S, bad));
+    }
+};
+
+template <int R, int BLOCK>
+__global__ __launch_bounds__(BLOCK) void reduce_half_kernel(const DevTensor *__restrict__ tensors,
+                                                            const Chunk *__restrict__ chunks, StepScalars s,
+                                                            FlagScratch *__restrict__ fs, int32_t *__restrict__ flag)
+{
+    const Where wh = locate(tensors, chunks, s.chunk_elems);
+    ReduceHalfOp<R> op;
     op.init(wh.t, wh.base);
     stream_chunk<BLOCK>(op, wh.len);
     publish_flag<BLOCK>(op.bad, fs, flag);

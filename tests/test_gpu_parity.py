@@ -393,3 +393,46 @@ def test_fp32_gradients_overflow_cases():
         hps = [hyper_pair(step=1), hyper_pair(step=2), hyper_pair(step=2)]
         run_steps(shard, ost, cc.cc_fused_adam_step, oracle.adam_step, hps, "adam fp32 " + case, fill, expect_flags=[0, 1, 0])
         shard.destroy()
+
+
+# ---------------------------------------------------------------------------- fp16 intermediate (the fp16 all-reduce baseline)
+
+def _unfused_f16(plan, hp, flag, stream=None):
+    cc.cc_unfused_adam_step_ex(plan, hp, flag, stream, cc.CC_GRAD_F16)
+
+
+def _oracle_f16(tensors, hp, threads=1):
+    return oracle.adam_step(tensors, hp, threads=threads, sum_f16=True)
+
+
+@pytest.mark.parametrize("R,gstd", [(1, 1e-2), (8, 0.7), (16, 3.0)])
+def test_unfused_adam_with_fp16_intermediate(R, gstd):
+    numels = ODD_LIST + [40000]
+    shard = Shard(numels, wds_for(numels), R, align_elems=8)
+    seeded_state(shard, 19)
+    ost = OracleState(shard, range(len(numels)))
+    hps = [hyper_pair(step=t, loss_scale=4.0) for t in (1, 2)]
+    run_steps(shard, ost, _unfused_f16, _oracle_f16, hps, "unfused fp16 intermediate R=%d" % R,
+              lambda i: seeded_grads(shard, 190 + i, gstd))
+    shard.destroy()
+
+
+def test_fp16_intermediate_overflows_where_the_fused_sum_does_not():
+    """Two slices of 60000 sum to 120000: finite in the fused kernel's fp32 registers, inf once it has to pass
+    through fp16.  The baseline skips the step, the fused path takes it."""
+    for fn, ofn, want in ((_unfused_f16, _oracle_f16, 1), (cc.cc_fused_adam_step, oracle.adam_step, 0)):
+        shard = Shard([3000, 64], [0.01, 0.0], 2, align_elems=8)
+        seeded_state(shard, 20)
+        ost = OracleState(shard, range(2))
+
+        def fill(i):
+            seeded_grads(shard, 200 + i, 1e-2)
+            for r in range(2):
+                shard.grad_of(r, 1)[5] = 60000.0
+        run_steps(shard, ost, fn, ofn, [hyper_pair(step=1, loss_scale=65536.0)], "fp16 range", fill, expect_flags=[want])
+        shard.destroy()
+    plan_f32 = Shard([64], [0.0], 2, align_elems=8, grad_dtype=torch.float32)
+    with pytest.raises(cc.CcError) as e:
+        _unfused_f16(plan_f32.plans[0], cc.Hyper(), plan_f32.flag)
+    assert e.value.code == cc.CC_ERR_ARG
+    plan_f32.destroy()
