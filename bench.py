@@ -58,6 +58,9 @@ def main() -> int:
     ap.add_argument("--grad-dtype", choices=("f16", "f32"), default="f16", help="element type of the R gradient slices")
     ap.add_argument("--flat", action="store_true", help="the same number of parameters as ONE contiguous tensor (Table 2's single-tensor case)")
     ap.add_argument("--graph", action="store_true", help="enqueue the timed steps as replays of a captured HIP graph of 20 steps")
+    ap.add_argument("--schedule", choices=("auto", "per-chunk", "ordered"), default="auto",
+                    help="how the kernels are laid over the device (cc_plan_set_schedule); auto = the library's choice")
+    ap.add_argument("--workgroups", type=int, default=0, help="workgroups of the ordered schedule (0 = one per compute unit)")
     ap.add_argument("--no-extras", action="store_true", help="only the headline step (for profiling runs)")
     ap.add_argument("--copy-only", action="store_true", help="run only the plain copy kernel (2 GiB, 20 launches): counter calibration")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
@@ -100,7 +103,11 @@ def main() -> int:
     GRAD_BYTES = 2 if args.grad_dtype == "f16" else 4
     shard = Shard([s.numel for s in cfg.params], [cfg.wd_of(s) for s in cfg.params], R, device=dev,
                   chunk_elems=args.chunk_elems, in_place=args.in_place,
-                  grad_dtype=torch.float16 if args.grad_dtype == "f16" else torch.float32)
+                  grad_dtype=torch.float16 if args.grad_dtype == "f16" else torch.float32,
+                  schedule={"auto": cc.CC_SCHEDULE_AUTO, "per-chunk": cc.CC_SCHEDULE_PER_CHUNK, "ordered": cc.CC_SCHEDULE_ORDERED}[args.schedule],
+                  workgroups=args.workgroups)
+    sched, wgs = cc.cc_plan_schedule(shard.plans[0])
+    ordered = sched == cc.CC_SCHEDULE_ORDERED
     W.fill_state(shard, cfg)
     W.fill_grads(shard, cfg, 1)
     torch.cuda.synchronize()
@@ -175,12 +182,15 @@ def main() -> int:
                                                  " [fp32 gradient slices]" if args.grad_dtype == "f32" else ""),
                    "chunk_elems": (N + chunks - 1) // chunks if cfg.index == 1 and chunks else (args.chunk_elems or cc.cc_default_chunk_elems()),
                    "chunks": chunks, "launch": "hip graph replay" if args.graph else "eager",
+                   "schedule": ("ordered: %d persistent workgroups take the chunks in table order" % wgs) if ordered
+                   else "one workgroup per chunk",
                    "table_bytes": table_bytes, "algorithmic_bytes_per_param": bpp},
         "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(gbs / HBM_PEAK_GBS, 4),
                      "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.index) if (args.chunk_elems == 0 and not args.in_place and not args.flat
                                                                          and args.grad_dtype == "f16") else None,
-                     "kernel": "fused_adam_kernel<R=%d>" % R if cfg.optimizer == "adam" else "lamb_phase1_kernel + lamb_phase2_kernel",
+                     "kernel": ("fused_adam%s_kernel<R=%d>" % ("_ordered" if ordered else "", R)) if cfg.optimizer == "adam"
+                     else "lamb_phase1%s_kernel + lamb_phase2%s_kernel" % (("_ordered",) * 2 if ordered else ("", "")),
                      "bytes_per_launch": bpp * N, "avg_launch_ms": round(ms, 5)},
     }
 

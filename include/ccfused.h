@@ -124,6 +124,21 @@ int cc_plan_create_ex(const cc_tensor *tensors, int32_t T, int32_t R, int32_t ch
                       cc_plan **out);
 int cc_plan_destroy(cc_plan *plan);
 
+/*
+ * How a plan's kernels are laid over the device (a tuning choice like the paper's autotuner picking protocol and
+ * channels, Section 5.3; results do not depend on it beyond the order of LAMB's per-chunk partial sums, which
+ * both schedules keep identical).
+ *   CC_SCHEDULE_PER_CHUNK  one workgroup per chunk, launched as a grid of that many workgroups.
+ *   CC_SCHEDULE_ORDERED    `workgroups` persistent workgroups (0 = one per compute unit) take the chunks in table
+ *                          order from a counter and keep the next chunk's loads in flight; needs the default
+ *                          chunk size of large shards (cc_default_chunk_elems()).
+ *   CC_SCHEDULE_AUTO       (default) ordered for large shards, per chunk for small ones.
+ * cc_plan_schedule reports what the plan will use (schedule: ORDERED or PER_CHUNK; workgroups per launch).
+ */
+typedef enum cc_schedule { CC_SCHEDULE_AUTO = 0, CC_SCHEDULE_PER_CHUNK = 1, CC_SCHEDULE_ORDERED = 2 } cc_schedule;
+int cc_plan_set_schedule(cc_plan *plan, int32_t schedule, int32_t workgroups);
+int cc_plan_schedule(const cc_plan *plan, int32_t *schedule, int32_t *workgroups);
+
 /* Totals of a plan: elements, chunks and bytes of table memory on the device. */
 int cc_plan_info(const cc_plan *plan, uint64_t *numel, int64_t *chunks, uint64_t *table_bytes);
 

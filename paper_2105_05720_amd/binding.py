@@ -12,6 +12,7 @@ from typing import List, Optional, Sequence
 
 CC_MAX_R = 16
 CC_GRAD_F16, CC_GRAD_F32 = 0, 1
+CC_SCHEDULE_AUTO, CC_SCHEDULE_PER_CHUNK, CC_SCHEDULE_ORDERED = 0, 1, 2
 CC_OK, CC_ERR_NULL, CC_ERR_ARG, CC_ERR_ALIGN, CC_ERR_ALIAS, CC_ERR_HIP, CC_ERR_NOMEM = 0, -1, -2, -3, -4, -5, -6
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -54,6 +55,8 @@ EXPORTS = {
     "cc_plan_create": (C.c_int, [C.POINTER(cc_tensor), C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_void_p)]),
     "cc_plan_create_ex": (C.c_int, [C.POINTER(cc_tensor), C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_void_p)]),
     "cc_plan_destroy": (C.c_int, [C.c_void_p]),
+    "cc_plan_set_schedule": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32]),
+    "cc_plan_schedule": (C.c_int, [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
     "cc_plan_info": (C.c_int, [C.c_void_p, C.POINTER(C.c_uint64), C.POINTER(C.c_int64), C.POINTER(C.c_uint64)]),
     "cc_fused_adam_step": (C.c_int, [C.c_void_p, C.POINTER(cc_hparams), C.c_void_p, C.c_void_p]),
     "cc_fused_lamb_step": (C.c_int, [C.c_void_p, C.POINTER(cc_hparams), C.c_void_p, C.c_void_p]),
@@ -211,6 +214,17 @@ def cc_plan_create_ex(tensors: Sequence[Tensor], R: int, chunk_elems: int = 0, g
 
 def cc_plan_destroy(plan: Plan) -> None:
     plan.destroy()
+
+
+def cc_plan_set_schedule(plan: Plan, schedule: int = CC_SCHEDULE_AUTO, workgroups: int = 0) -> None:
+    _check(load().cc_plan_set_schedule(plan.handle, schedule, workgroups))
+
+
+def cc_plan_schedule(plan: Plan):
+    """(schedule the plan will use: CC_SCHEDULE_ORDERED or CC_SCHEDULE_PER_CHUNK, workgroups per launch)."""
+    sched, wgs = C.c_int32(), C.c_int32()
+    _check(load().cc_plan_schedule(plan.handle, C.byref(sched), C.byref(wgs)))
+    return sched.value, wgs.value
 
 
 def cc_plan_info(plan: Plan):

@@ -5,6 +5,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -21,6 +22,8 @@ constexpr int32_t kSmallChunkElems = 1024;       // one sweep of a 128-thread wo
 constexpr uint64_t kSmallShardElems = 64u << 20; // below this many elements the default chunk is the small one (size sweep)
 constexpr int32_t kMaxChunkElems = 1 << 24;      // lane offsets inside a chunk are 32-bit byte offsets
 constexpr int kBigBlock = 512, kSmallBlock = 128;
+constexpr int kOrderedMaxF32Slices = 8;           // two chunks of more fp32 slices than this do not fit the register file
+constexpr int64_t kOrderedMinChunksPerCu = 8;    // below this many chunks per compute unit a plan keeps one workgroup per chunk
 
 thread_local char g_err[512] = "";
 
@@ -63,6 +66,13 @@ struct cc_plan {
     int32_t T = 0, R = 0, chunk_elems = 0;
     int block = kBigBlock;                  // threads per workgroup of the streaming kernels
     FlagScratch *d_flag_scratch = nullptr;  // {done, bad}, zero between launches
+    bool ordered = false;                   // large shards: persistent workgroups take chunks in table order
+    int32_t schedule = CC_SCHEDULE_AUTO;    // what the caller asked for
+    unsigned ordered_grid = 0;              // workgroups of the ordered schedule (one per compute unit unless set)
+    int32_t cus = 0;                        // compute units of the device the plan was created on
+    uint32_t nfull = 0;                     // full chunks; the ordered table lists them first, short last chunks behind
+    Chunk *d_chunks_ordered = nullptr;
+    WorkQueue *d_queue = nullptr;           // zero between launches
     int64_t chunks = 0;
     uint64_t numel = 0;
     bool in_place = false;                  // some tensor has out == in
@@ -76,6 +86,29 @@ struct cc_plan {
     double *d_sums = nullptr;               // 2 per tensor (LAMB)
     float *d_gsum = nullptr;                // unfused pipelines, allocated on first use
 };
+
+namespace {
+
+// Workgroups of an ordered launch: one per compute unit unless the caller chose a number; never more than there
+// are pairs of chunks (every workgroup owns two entries without asking).
+unsigned ordered_grid(const cc_plan *p)
+{
+    unsigned g = p->ordered_grid ? p->ordered_grid : (unsigned)p->cus;
+    const unsigned most = (unsigned)((p->chunks + 1) / 2);
+    if (g > most) g = most;
+    return g ? g : 1u;
+}
+
+void resolve_schedule(cc_plan *p)
+{
+    if (p->schedule == CC_SCHEDULE_ORDERED) p->ordered = true;
+    else if (p->schedule == CC_SCHEDULE_PER_CHUNK) p->ordered = false;
+    else p->ordered = p->chunk_elems == kDefaultChunkElems && p->chunks >= kOrderedMinChunksPerCu * (int64_t)p->cus &&
+                      !(p->grad_f32 && p->R > kOrderedMaxF32Slices);
+    if (p->chunk_elems != kDefaultChunkElems || p->chunks == 0) p->ordered = false;
+}
+
+}  // namespace
 
 extern "C" {
 
@@ -195,6 +228,26 @@ int cc_plan_create_ex(const cc_tensor *tensors, int32_t T, int32_t R, int32_t ch
     p->numel = total;
     p->gsum_elems = goff;
     cc_chunk_table_fill(numels.data(), T, ce, table.data(), chunks);
+    // The ordered schedule's table: the same entries, full chunks first (tensor order = address order inside each
+    // arena), then the short last chunks, which take the unpipelined path.
+    std::vector<uint32_t> ordered_table;
+    try {
+        ordered_table.resize((size_t)(2 * chunks) + 2);
+    } catch (const std::bad_alloc &) {
+        delete p;
+        return fail(CC_ERR_NOMEM, "cc_plan_create: out of host memory");
+    }
+    {
+        size_t k = 0;
+        for (int pass = 0; pass < 2; ++pass) {
+            for (int64_t i = 0; i < chunks; ++i) {
+                const uint32_t t = table[2 * (size_t)i], idx = table[2 * (size_t)i + 1];
+                const bool full = ((uint64_t)idx + 1) * (uint64_t)ce <= numels[t];
+                if (full == (pass == 0)) { ordered_table[2 * k] = t; ordered_table[2 * k + 1] = idx; ++k; }
+            }
+            if (pass == 0) p->nfull = (uint32_t)k;
+        }
+    }
 
 #define PLAN_TRY(expr)                                                                             \
     do {                                                                                           \
@@ -214,8 +267,41 @@ int cc_plan_create_ex(const cc_tensor *tensors, int32_t T, int32_t R, int32_t ch
     PLAN_TRY(hipMemset(p->d_sums, 0, sizeof(double) * 2 * (size_t)T));
     PLAN_TRY(hipMalloc((void **)&p->d_flag_scratch, sizeof(FlagScratch)));
     PLAN_TRY(hipMemset(p->d_flag_scratch, 0, sizeof(FlagScratch)));
+    PLAN_TRY(hipMalloc((void **)&p->d_chunks_ordered, sizeof(Chunk) * (size_t)(chunks + 1)));
+    if (chunks > 0) PLAN_TRY(hipMemcpy(p->d_chunks_ordered, ordered_table.data(), sizeof(Chunk) * (size_t)chunks, hipMemcpyHostToDevice));
+    PLAN_TRY(hipMalloc((void **)&p->d_queue, sizeof(WorkQueue)));
+    PLAN_TRY(hipMemset(p->d_queue, 0, sizeof(WorkQueue)));
+    {
+        int dev = 0, cus = 0;
+        PLAN_TRY(hipGetDevice(&dev));
+        PLAN_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+        p->cus = cus > 0 ? cus : 1;
+    }
 #undef PLAN_TRY
+    resolve_schedule(p);
     *out = p;
+    return CC_OK;
+}
+
+int cc_plan_set_schedule(cc_plan *p, int32_t schedule, int32_t workgroups)
+{
+    if (!p) return fail(CC_ERR_NULL, "cc_plan_set_schedule: plan is NULL");
+    if (schedule != CC_SCHEDULE_AUTO && schedule != CC_SCHEDULE_PER_CHUNK && schedule != CC_SCHEDULE_ORDERED)
+        return fail(CC_ERR_ARG, "cc_plan_set_schedule: schedule = %d", schedule);
+    if (workgroups < 0 || workgroups > 65536) return fail(CC_ERR_ARG, "cc_plan_set_schedule: workgroups = %d outside 0..65536", workgroups);
+    if (schedule == CC_SCHEDULE_ORDERED && p->chunk_elems != kDefaultChunkElems)
+        return fail(CC_ERR_ARG, "the ordered schedule needs chunk_elems = %d (plan has %d)", kDefaultChunkElems, p->chunk_elems);
+    p->schedule = schedule;
+    p->ordered_grid = (unsigned)workgroups;
+    resolve_schedule(p);
+    return CC_OK;
+}
+
+int cc_plan_schedule(const cc_plan *p, int32_t *schedule, int32_t *workgroups)
+{
+    if (!p) return fail(CC_ERR_NULL, "cc_plan_schedule: plan is NULL");
+    if (schedule) *schedule = p->ordered ? CC_SCHEDULE_ORDERED : CC_SCHEDULE_PER_CHUNK;
+    if (workgroups) *workgroups = p->ordered ? (int32_t)ordered_grid(p) : (int32_t)p->chunks;
     return CC_OK;
 }
 
@@ -228,6 +314,8 @@ int cc_plan_destroy(cc_plan *p)
     if (p->d_sums) (void)hipFree(p->d_sums);
     if (p->d_gsum) (void)hipFree(p->d_gsum);
     if (p->d_flag_scratch) (void)hipFree(p->d_flag_scratch);
+    if (p->d_chunks_ordered) (void)hipFree(p->d_chunks_ordered);
+    if (p->d_queue) (void)hipFree(p->d_queue);
     delete p;
     return CC_OK;
 }
@@ -237,7 +325,7 @@ int cc_plan_info(const cc_plan *p, uint64_t *numel, int64_t *chunks, uint64_t *t
     if (!p) return fail(CC_ERR_NULL, "cc_plan_info: plan is NULL");
     if (numel) *numel = p->numel;
     if (chunks) *chunks = p->chunks;
-    if (table_bytes) *table_bytes = sizeof(Chunk) * (uint64_t)p->chunks + sizeof(DevTensor) * (uint64_t)p->T;
+    if (table_bytes) *table_bytes = sizeof(Chunk) * (uint64_t)p->chunks + sizeof(DevTensor) * (uint64_t)p->T;   // of the schedule in use
     return CC_OK;
 }
 
@@ -321,9 +409,33 @@ int ensure_gsum(cc_plan *p)
         else { constexpr int BLK = kSmallBlock; CALL; }                       \
     } while (0)
 
+// Chunks per ticket of the ordered schedule, by how many bytes a kernel moves per element: one counter serves the
+// whole device at about one ticket per 12 ns, so a ticket has to stand for well over 100 KB of traffic.
+enum SpanKind { kSpanAdam, kSpanPhase1, kSpanPhase2, kSpanReduce, kSpanFromSum, kSpanCast, kSpanKinds };
+uint32_t span_of(SpanKind k)
+{
+    static const uint32_t defaults[kSpanKinds] = {1, 1, 2, 2, 1, 4};
+    static const char *names[kSpanKinds] = {"CCFUSED_SPAN_ADAM", "CCFUSED_SPAN_PHASE1", "CCFUSED_SPAN_PHASE2", "CCFUSED_SPAN_REDUCE", "CCFUSED_SPAN_FROMSUM", "CCFUSED_SPAN_CAST"};
+    const char *e = getenv(names[k]);
+    if (e && atoi(e) > 0) return (uint32_t)atoi(e);
+    return defaults[k];
+}
+
+// Arguments every ordered kernel starts with.
+#define ORDERED_ARGS(p, kind) (p)->d_tensors, (p)->d_chunks_ordered, (p)->nfull, (uint32_t)(p)->chunks, span_of(kind)
+
 template <int MODE, int BLK, bool GF32>
 void launch_fused_adam_r(const cc_plan *p, const StepScalars &s, int32_t *flag, hipStream_t st)
 {
+    if (p->ordered) {
+        const dim3 grid(ordered_grid(p)), block(kBigBlock);
+        switch (p->R) {
+#define CASE(r) case r: hipLaunchKernelGGL((fused_adam_ordered_kernel<r, MODE, kBigBlock, GF32>), grid, block, 0, st, ORDERED_ARGS(p, kSpanAdam), s, p->d_queue, flag); break;
+            FOR_EACH_R(CASE)
+#undef CASE
+        }
+        return;
+    }
     const dim3 grid((unsigned)p->chunks), block(BLK);
     switch (p->R) {
 #define CASE(r) case r: hipLaunchKernelGGL((fused_adam_kernel<r, MODE, BLK, GF32>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, p->d_flag_scratch, flag); break;
@@ -342,6 +454,15 @@ void launch_fused_adam(const cc_plan *p, const StepScalars &s, int32_t *flag, hi
 template <int BLK, bool GF32>
 void launch_lamb_phase1_r(const cc_plan *p, const StepScalars &s, int32_t *flag, hipStream_t st)
 {
+    if (p->ordered) {
+        const dim3 grid(ordered_grid(p)), block(kBigBlock);
+        switch (p->R) {
+#define CASE(r) case r: hipLaunchKernelGGL((lamb_phase1_ordered_kernel<r, kBigBlock, GF32>), grid, block, 0, st, ORDERED_ARGS(p, kSpanPhase1), s, p->d_partials, p->d_queue, flag); break;
+            FOR_EACH_R(CASE)
+#undef CASE
+        }
+        return;
+    }
     const dim3 grid((unsigned)p->chunks), block(BLK);
     switch (p->R) {
 #define CASE(r) case r: hipLaunchKernelGGL((lamb_phase1_kernel<r, BLK, GF32>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, p->d_partials, p->d_flag_scratch, flag); break;
@@ -360,6 +481,15 @@ void launch_lamb_phase1(const cc_plan *p, const StepScalars &s, int32_t *flag, h
 template <int BLK, bool GF32>
 void launch_reduce_r(const cc_plan *p, const StepScalars &s, int32_t *flag, hipStream_t st)
 {
+    if (p->ordered) {
+        const dim3 grid(ordered_grid(p)), block(kBigBlock);
+        switch (p->R) {
+#define CASE(r) case r: hipLaunchKernelGGL((reduce_ordered_kernel<r, kBigBlock, GF32>), grid, block, 0, st, ORDERED_ARGS(p, kSpanReduce), s, p->d_queue, flag); break;
+            FOR_EACH_R(CASE)
+#undef CASE
+        }
+        return;
+    }
     const dim3 grid((unsigned)p->chunks), block(BLK);
     switch (p->R) {
 #define CASE(r) case r: hipLaunchKernelGGL((reduce_kernel<r, BLK, GF32>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, p->d_flag_scratch, flag); break;
@@ -378,6 +508,16 @@ void launch_reduce(const cc_plan *p, const StepScalars &s, int32_t *flag, hipStr
 template <int BLK, bool SUM16>
 void launch_adam_from_sum(const cc_plan *p, const StepScalars &s, const int32_t *flag, hipStream_t st, int mode)
 {
+    if (p->ordered) {
+        const dim3 grid(ordered_grid(p)), block(kBigBlock);
+        switch (mode) {
+            case 0: hipLaunchKernelGGL((adam_from_sum_ordered_kernel<0, kBigBlock, SUM16>), grid, block, 0, st, ORDERED_ARGS(p, kSpanFromSum), s, p->d_queue, flag); break;
+            case 1: hipLaunchKernelGGL((adam_from_sum_ordered_kernel<1, kBigBlock, SUM16>), grid, block, 0, st, ORDERED_ARGS(p, kSpanFromSum), s, p->d_queue, flag); break;
+            case 2: hipLaunchKernelGGL((adam_from_sum_ordered_kernel<2, kBigBlock, SUM16>), grid, block, 0, st, ORDERED_ARGS(p, kSpanFromSum), s, p->d_queue, flag); break;
+            default: hipLaunchKernelGGL((adam_from_sum_ordered_kernel<3, kBigBlock, SUM16>), grid, block, 0, st, ORDERED_ARGS(p, kSpanFromSum), s, p->d_queue, flag); break;
+        }
+        return;
+    }
     const dim3 grid((unsigned)p->chunks), block(BLK);
     switch (mode) {
         case 0: hipLaunchKernelGGL((adam_from_sum_kernel<0, BLK, SUM16>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag); break;
@@ -390,6 +530,15 @@ void launch_adam_from_sum(const cc_plan *p, const StepScalars &s, const int32_t 
 template <int BLK>
 void launch_reduce_half(const cc_plan *p, const StepScalars &s, int32_t *flag, hipStream_t st)
 {
+    if (p->ordered) {
+        const dim3 grid(ordered_grid(p)), block(kBigBlock);
+        switch (p->R) {
+#define CASE(r) case r: hipLaunchKernelGGL((reduce_half_ordered_kernel<r, kBigBlock>), grid, block, 0, st, ORDERED_ARGS(p, kSpanReduce), s, p->d_queue, flag); break;
+            FOR_EACH_R(CASE)
+#undef CASE
+        }
+        return;
+    }
     const dim3 grid((unsigned)p->chunks), block(BLK);
     switch (p->R) {
 #define CASE(r) case r: hipLaunchKernelGGL((reduce_half_kernel<r, BLK>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, p->d_flag_scratch, flag); break;
@@ -420,6 +569,12 @@ int clear_flag(int32_t *flag, hipStream_t st)
 int lamb_phase2_impl(cc_plan *p, const StepScalars &s, const int32_t *flag, hipStream_t st, bool emit16)
 {
     if (p->chunks == 0) return CC_OK;
+    if (p->ordered) {
+        const dim3 grid(ordered_grid(p)), block(kBigBlock);
+        if (emit16) hipLaunchKernelGGL((lamb_phase2_ordered_kernel<true, kBigBlock>), grid, block, 0, st, ORDERED_ARGS(p, kSpanPhase2), s, p->d_sums, p->d_queue, flag);
+        else hipLaunchKernelGGL((lamb_phase2_ordered_kernel<false, kBigBlock>), grid, block, 0, st, ORDERED_ARGS(p, kSpanPhase2), s, p->d_sums, p->d_queue, flag);
+        return launched("lamb_phase2_ordered_kernel");
+    }
     const dim3 grid((unsigned)p->chunks);
     if (emit16) BY_BLOCK(p, hipLaunchKernelGGL((lamb_phase2_kernel<true, BLK>), grid, dim3(BLK), 0, st, p->d_tensors, p->d_chunks, s, p->d_sums, flag));
     else BY_BLOCK(p, hipLaunchKernelGGL((lamb_phase2_kernel<false, BLK>), grid, dim3(BLK), 0, st, p->d_tensors, p->d_chunks, s, p->d_sums, flag));
@@ -434,6 +589,10 @@ int lamb_norms(cc_plan *p, hipStream_t st)
 
 int cast_launch(cc_plan *p, const StepScalars &s, const int32_t *flag, hipStream_t st, int guarded)
 {
+    if (p->ordered) {
+        hipLaunchKernelGGL((cast_ordered_kernel<kBigBlock>), dim3(ordered_grid(p)), dim3(kBigBlock), 0, st, ORDERED_ARGS(p, kSpanCast), s, p->d_queue, flag, guarded);
+        return launched("cast_ordered_kernel");
+    }
     const dim3 grid((unsigned)p->chunks);
     BY_BLOCK(p, hipLaunchKernelGGL((cast_kernel<BLK>), grid, dim3(BLK), 0, st, p->d_tensors, p->d_chunks, s, flag, guarded));
     return launched("cast_kernel");
@@ -525,7 +684,8 @@ int cc_unfused_lamb_step(cc_plan *p, const cc_hparams *hp, int32_t *flag, void *
     const dim3 grid((unsigned)p->chunks);
     BY_BLOCK(p, launch_reduce<BLK>(p, s, flag, st));
     if ((rc = launched("reduce_kernel"))) return rc;
-    BY_BLOCK(p, hipLaunchKernelGGL((lamb_phase1_from_sum_kernel<BLK>), grid, dim3(BLK), 0, st, p->d_tensors, p->d_chunks, s, p->d_partials));
+    if (p->ordered) hipLaunchKernelGGL((lamb_phase1_from_sum_ordered_kernel<kBigBlock>), dim3(ordered_grid(p)), dim3(kBigBlock), 0, st, ORDERED_ARGS(p, kSpanFromSum), s, p->d_partials, p->d_queue);
+    else BY_BLOCK(p, hipLaunchKernelGGL((lamb_phase1_from_sum_kernel<BLK>), grid, dim3(BLK), 0, st, p->d_tensors, p->d_chunks, s, p->d_partials));
     if ((rc = launched("lamb_phase1_from_sum_kernel"))) return rc;
     if ((rc = lamb_norms(p, st))) return rc;
     if ((rc = lamb_phase2_impl(p, s, flag, st, false))) return rc;

@@ -16,6 +16,11 @@
 //     2 x (R + 3) independent requests in flight.
 //   * The reduced gradient stays in registers (Section 3.3, AllReduce Fuse: the output of the reduction is
 //     handed to the computation directly, never through memory).
+//   * Large shards run under the ordered persistent schedule (ordered_stream below): one workgroup per compute
+//     unit, chunks handed out in table order from one counter, the next chunk's loads in flight while the current
+//     one is computed.  What it buys is on the DRAM side: the addresses in flight at any moment form a narrow
+//     window that slides through each stream, instead of the wide, drifting set that a grid of independent
+//     workgroups produces.  Small shards keep one workgroup per chunk (more parallel start-up, no ticket latency).
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -131,21 +136,30 @@ __device__ __forceinline__ void st_f16x4(gbytes b, uint32_t off, const float (&x
 struct Where {
     const DevTensor *t;
     uint32_t tensor;          // index of t in the plan's tensor list
+    uint32_t slot;            // position of the chunk in tensor order (first_chunk + index): where its LAMB partials go
     uint64_t base;            // first element of the chunk inside the tensor
     uint32_t len;             // elements in this chunk (the tensor's last chunk may be short)
 };
 
-__device__ __forceinline__ Where locate(const DevTensor *__restrict__ tensors, const Chunk *__restrict__ chunks,
-                                        uint32_t chunk_elems)
+// Table entry `entry` (uniform over the workgroup) resolved through the tensor descriptor.
+__device__ __forceinline__ Where locate_at(const DevTensor *__restrict__ tensors, const Chunk *__restrict__ chunks,
+                                           uint32_t entry, uint32_t chunk_elems)
 {
-    const Chunk c = chunks[blockIdx.x];
+    const Chunk c = chunks[entry];
     Where wh;
     wh.t = tensors + c.tensor;
     wh.tensor = c.tensor;
+    wh.slot = wh.t->first_chunk + c.index;
     wh.base = (uint64_t)c.index * chunk_elems;
     const uint64_t rem = wh.t->numel - wh.base;
     wh.len = rem < chunk_elems ? (uint32_t)rem : chunk_elems;
     return wh;
+}
+
+__device__ __forceinline__ Where locate(const DevTensor *__restrict__ tensors, const Chunk *__restrict__ chunks,
+                                        uint32_t chunk_elems)
+{
+    return locate_at(tensors, chunks, blockIdx.x, chunk_elems);
 }
 
 // The overflow flag is produced by the same launch that does the work, with no clearing launch in front of it.
@@ -233,6 +247,129 @@ __device__ __forceinline__ void stream_chunk(Op &op, uint32_t len)
             op.store(a, e);
         } else {
             for (uint32_t j = e; j < len; ++j) op.single(j);
+        }
+    }
+}
+
+// ---- the ordered persistent schedule -------------------------------------------------------------------------------
+// gridDim.x workgroups (one per compute unit) share the chunk table through one counter.  The table is cut into
+// blocks of `span` consecutive entries.  Workgroup b starts with blocks b and b + G (G = gridDim.x) and then takes
+// block 2G + ticket, ticket = atomic increment of `next`: blocks are started in table order by whichever workgroup
+// is free, so the chunks in flight are always ~2G span consecutive ones.  (A counter that every workgroup of the
+// device increments serves about one ticket per 12 ns; span is chosen per kernel so that a ticket covers enough
+// bytes for that not to matter.)  The table lists every full chunk first (nfull of them, in address order) and
+// the short last chunks of tensors behind them; full chunks go through a two-stage pipeline (loads of the next
+// chunk are issued before the current chunk is computed and stored), the few short ones through stream_chunk.
+// Nothing waits on another workgroup: a workgroup leaves when its entries are past the table, so the grid drains
+// whatever its size.  `done` counts finished workgroups in its low half and those that saw an inf/NaN in its high
+// half (one atomic, so no fence has to order two words); the workgroup that completes the count writes the
+// caller's flag and zeroes the queue for the next launch.
+struct WorkQueue {
+    struct alignas(128) Next { uint32_t v; } next;
+    struct alignas(128) Done { unsigned long long v; } done;
+};
+
+// The increasing sequence of table entries one workgroup works through.  The ticket for the block after the next
+// one is requested when a block is entered and only looked at when that later block is entered, a block's worth of
+// work later, so no wave waits on the atomic; its value reaches the other waves through LDS (two slots used in
+// turn: one barrier per block).
+struct Entries {
+    WorkQueue *q;
+    uint32_t *slots;          // LDS, 2 words
+    uint32_t span, blk, j, second, ticket;
+    bool second_pending;      // the workgroup's second block (blockIdx.x + gridDim.x) has not been entered yet
+    int turn;
+    __device__ __forceinline__ void init(WorkQueue *queue, uint32_t *lds_slots, uint32_t span_)
+    {
+        q = queue; slots = lds_slots; span = span_;
+        blk = blockIdx.x; second = blockIdx.x + gridDim.x;    // the two blocks every workgroup owns without asking
+        second_pending = true;
+        j = 0; turn = 0; ticket = 0;
+    }
+    // every thread of the workgroup calls next() at the same point
+    __device__ __forceinline__ uint32_t next()
+    {
+        if (j == span) {                                      // enter the next block
+            j = 0;
+            if (second_pending) {
+                blk = second;
+                second_pending = false;
+            } else {
+                if (threadIdx.x == 0) slots[turn] = 2 * gridDim.x + ticket;
+                __syncthreads();
+                blk = (uint32_t)__builtin_amdgcn_readfirstlane((int)slots[turn]);
+                turn ^= 1;
+            }
+            if (threadIdx.x == 0) ticket = atomicAdd(&q->next.v, 1u);      // for the block after the next one
+        }
+        return blk * span + j++;
+    }
+};
+
+// An Op used here also provides   template <int BLOCK> void end_chunk(uint32_t slot);   called once per chunk after
+// its last store (LAMB phase 1 writes the chunk's partial sums there; the others do nothing).
+// bind(op, entry) points op at table entry `entry` and returns its Where.
+template <int BLOCK, int GROUPS, class Op, class Bind>
+__device__ __forceinline__ void ordered_stream(Op &opa, Op &opb, Bind bind, uint32_t nfull, uint32_t nchunks, uint32_t span,
+                                               WorkQueue *q)
+{
+    __shared__ uint32_t ticket_slots[2];
+    constexpr uint32_t kGroup = BLOCK * Op::kPack;
+    const uint32_t lane_e = threadIdx.x * Op::kPack;
+    Entries en;
+    en.init(q, ticket_slots, span);
+    uint32_t e = en.next(), n = en.next();         // current and next entry, e < n
+    if (e < nfull) {
+        typename Op::Regs xa[GROUPS], xb[GROUPS];
+        Where wa = bind(opa, e), wb;
+#pragma unroll
+        for (int g = 0; g < GROUPS; ++g) opa.load(xa[g], g * kGroup + lane_e);
+        while (true) {
+            wb = bind(opb, n < nfull ? n : e);     // past the full chunks: reload the own chunk, the values are not used
+#pragma unroll
+            for (int g = 0; g < GROUPS; ++g) opb.load(xb[g], g * kGroup + lane_e);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int g = 0; g < GROUPS; ++g) { opa.compute(xa[g]); opa.store(xa[g], g * kGroup + lane_e); }
+            opa.template end_chunk<BLOCK>(wa.slot);
+            __builtin_amdgcn_sched_barrier(0);
+            const uint32_t n2 = en.next();
+            if (n >= nfull) { e = n; n = n2; break; }
+            wa = bind(opa, n2 < nfull ? n2 : n);
+#pragma unroll
+            for (int g = 0; g < GROUPS; ++g) opa.load(xa[g], g * kGroup + lane_e);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int g = 0; g < GROUPS; ++g) { opb.compute(xb[g]); opb.store(xb[g], g * kGroup + lane_e); }
+            opb.template end_chunk<BLOCK>(wb.slot);
+            __builtin_amdgcn_sched_barrier(0);
+            e = n2;
+            n = en.next();
+            if (e >= nfull) break;
+        }
+    }
+    while (e < nchunks) {                          // short chunks, one at a time
+        const Where wh = bind(opa, e);
+        stream_chunk<BLOCK, Op, GROUPS>(opa, wh.len);
+        opa.template end_chunk<BLOCK>(wh.slot);
+        e = n;
+        n = en.next();
+    }
+}
+
+// Last act of a workgroup under the ordered schedule: count itself (and whether it saw an inf/NaN); the workgroup
+// that completes the count writes the flag (RAISE) and zeroes the queue.
+template <bool RAISE>
+__device__ __forceinline__ void leave_queue(bool bad, WorkQueue *q, int32_t *flag)
+{
+    const int any = RAISE ? __syncthreads_or(bad ? 1 : 0) : 0;
+    if (threadIdx.x == 0) {
+        const unsigned long long mine = 1ull | (any ? (1ull << 32) : 0ull);
+        const unsigned long long prev = atomicAdd(&q->done.v, mine);
+        if ((uint32_t)prev == gridDim.x - 1) {
+            if (RAISE) *flag = ((prev + mine) >> 32) != 0ull ? 1 : 0;
+            atomicExch(&q->done.v, 0ull);
+            atomicExch(&q->next.v, 0u);
         }
     }
 }
@@ -387,6 +524,7 @@ struct AdamOp {
         st_f32(m_out, j * 4, m); st_f32(v_out, j * 4, v); st_f32(w_out, j * 4, w);
         if (EMIT16) st_f16(w16, j * 2, w);
     }
+    template <int BLOCK> __device__ __forceinline__ void end_chunk(uint32_t) {}
 };
 
 template <int R, int MODE, int BLOCK, bool GF32 = false, int GROUPS = 2>
@@ -399,6 +537,24 @@ __global__ __launch_bounds__(BLOCK) void fused_adam_kernel(const DevTensor *__re
     op.init(wh.t, wh.base, s);
     stream_chunk<BLOCK, decltype(op), GROUPS>(op, wh.len);
     publish_flag<BLOCK>(op.bad, fs, flag);
+}
+
+// The same step under the ordered persistent schedule (chunk_elems == BLOCK * 4 * GROUPS).
+template <int R, int MODE, int BLOCK, bool GF32 = false, int GROUPS = 2>
+__global__ __launch_bounds__(BLOCK) void fused_adam_ordered_kernel(const DevTensor *__restrict__ tensors,
+                                                                   const Chunk *__restrict__ chunks, uint32_t nfull,
+                                                                   uint32_t nchunks, uint32_t span, StepScalars s,
+                                                                   WorkQueue *__restrict__ q, int32_t *__restrict__ flag)
+{
+    typedef AdamOp<GradSlices<R, GF32>, MODE, true> Op;
+    Op a, b;
+    auto bind = [&](Op &op, uint32_t entry) {
+        const Where wh = locate_at(tensors, chunks, entry, s.chunk_elems);
+        op.init(wh.t, wh.base, s);
+        return wh;
+    };
+    ordered_stream<BLOCK, GROUPS>(a, b, bind, nfull, nchunks, span, q);
+    leave_queue<true>(a.bad | b.bad, q, flag);
 }
 
 // Unfused pipeline, optimizer stage: the same update from the stored fp32 sum; the cast kernel emits fp16.
@@ -414,6 +570,24 @@ __global__ __launch_bounds__(BLOCK) void adam_from_sum_kernel(const DevTensor *_
     AdamOp<typename std::conditional<SUM16, GradSumHalf, GradSum>::type, MODE, false> op;
     op.init(wh.t, wh.base, s);
     stream_chunk<BLOCK>(op, wh.len);
+}
+
+template <int MODE, int BLOCK, bool SUM16 = false>
+__global__ __launch_bounds__(BLOCK) void adam_from_sum_ordered_kernel(const DevTensor *__restrict__ tensors,
+                                                                      const Chunk *__restrict__ chunks, uint32_t nfull,
+                                                                      uint32_t nchunks, uint32_t span, StepScalars s,
+                                                                      WorkQueue *__restrict__ q, const int32_t *__restrict__ flag)
+{
+    if (!(MODE & kModeGuard) && *flag != 0) return;
+    typedef AdamOp<typename std::conditional<SUM16, GradSumHalf, GradSum>::type, MODE, false> Op;
+    Op a, b;
+    auto bind = [&](Op &op, uint32_t entry) {
+        const Where wh = locate_at(tensors, chunks, entry, s.chunk_elems);
+        op.init(wh.t, wh.base, s);
+        return wh;
+    };
+    ordered_stream<BLOCK, 2>(a, b, bind, nfull, nchunks, span, q);
+    leave_queue<false>(false, q, nullptr);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -457,6 +631,7 @@ struct LambPhase1Op {
     float wd;
     bool bad = false;
     float sw = 0.f, su = 0.f;        // per lane: at most chunk_elems / BLOCK terms each, then double
+    double *partials = nullptr;      // 2 per chunk, indexed by the chunk's position in tensor order
     struct Regs { typename Grad::Regs g; float w[4], m[4], v[4]; };
 
     __device__ __forceinline__ void init(const DevTensor *t, uint64_t base, const StepScalars &sc)
@@ -499,6 +674,17 @@ struct LambPhase1Op {
         one(grad.sum1(j), w, m, v);
         st_f32(m_out, j * 4, m); st_f32(v_out, j * 4, v);
     }
+    // The chunk's two partial sums: lanes in fp32, then wave butterfly and LDS in double, always in the same order.
+    template <int BLOCK> __device__ __forceinline__ void end_chunk(uint32_t slot)
+    {
+        double dw = sw, du = su;
+        block_sum2<BLOCK>(dw, du);
+        if (threadIdx.x == 0) {
+            partials[2 * (uint64_t)slot] = dw;
+            partials[2 * (uint64_t)slot + 1] = du;
+        }
+        sw = su = 0.f;
+    }
 };
 
 template <class Grad, bool RAISE, int BLOCK>
@@ -509,14 +695,48 @@ __device__ __forceinline__ void lamb_phase1_body(const DevTensor *__restrict__ t
     const Where wh = locate(tensors, chunks, s.chunk_elems);
     LambPhase1Op<Grad> op;
     op.init(wh.t, wh.base, s);
+    op.partials = partials;
     stream_chunk<BLOCK>(op, wh.len);
-    double dw = op.sw, du = op.su;
-    block_sum2<BLOCK>(dw, du);
-    if (threadIdx.x == 0) {
-        partials[2 * (uint64_t)blockIdx.x] = dw;
-        partials[2 * (uint64_t)blockIdx.x + 1] = du;
-    }
+    op.template end_chunk<BLOCK>(wh.slot);
     if (RAISE) publish_flag<BLOCK>(op.bad, fs, flag);
+}
+
+template <class Grad, bool RAISE, int BLOCK>
+__device__ __forceinline__ void lamb_phase1_ordered_body(const DevTensor *__restrict__ tensors, const Chunk *__restrict__ chunks,
+                                                         uint32_t nfull, uint32_t nchunks, uint32_t span, const StepScalars &s,
+                                                         double *__restrict__ partials, WorkQueue *__restrict__ q,
+                                                         int32_t *__restrict__ flag)
+{
+    typedef LambPhase1Op<Grad> Op;
+    Op a, b;
+    a.partials = b.partials = partials;
+    auto bind = [&](Op &op, uint32_t entry) {
+        const Where wh = locate_at(tensors, chunks, entry, s.chunk_elems);
+        op.init(wh.t, wh.base, s);
+        return wh;
+    };
+    ordered_stream<BLOCK, 2>(a, b, bind, nfull, nchunks, span, q);
+    leave_queue<RAISE>(a.bad | b.bad, q, flag);
+}
+
+template <int R, int BLOCK, bool GF32 = false>
+__global__ __launch_bounds__(BLOCK) void lamb_phase1_ordered_kernel(const DevTensor *__restrict__ tensors,
+                                                                    const Chunk *__restrict__ chunks, uint32_t nfull,
+                                                                    uint32_t nchunks, uint32_t span, StepScalars s,
+                                                                    double *__restrict__ partials, WorkQueue *__restrict__ q,
+                                                                    int32_t *__restrict__ flag)
+{
+    lamb_phase1_ordered_body<GradSlices<R, GF32>, true, BLOCK>(tensors, chunks, nfull, nchunks, span, s, partials, q, flag);
+}
+
+template <int BLOCK>
+__global__ __launch_bounds__(BLOCK) void lamb_phase1_from_sum_ordered_kernel(const DevTensor *__restrict__ tensors,
+                                                                             const Chunk *__restrict__ chunks, uint32_t nfull,
+                                                                             uint32_t nchunks, uint32_t span, StepScalars s,
+                                                                             double *__restrict__ partials,
+                                                                             WorkQueue *__restrict__ q)
+{
+    lamb_phase1_ordered_body<GradSum, false, BLOCK>(tensors, chunks, nfull, nchunks, span, s, partials, q, nullptr);
 }
 
 template <int R, int BLOCK, bool GF32 = false>
@@ -611,6 +831,7 @@ struct LambPhase2Op {
         st_f32(w_out, j * 4, wn);
         if (EMIT16) st_f16(w16, j * 2, wn);
     }
+    template <int BLOCK> __device__ __forceinline__ void end_chunk(uint32_t) {}
 };
 
 template <bool EMIT16, int BLOCK>
@@ -626,6 +847,27 @@ __global__ __launch_bounds__(BLOCK) void lamb_phase2_kernel(const DevTensor *__r
     LambPhase2Op<EMIT16> op;
     op.init(wh.t, wh.base, s, ratio);
     stream_chunk<BLOCK>(op, wh.len);
+}
+
+template <bool EMIT16, int BLOCK>
+__global__ __launch_bounds__(BLOCK) void lamb_phase2_ordered_kernel(const DevTensor *__restrict__ tensors,
+                                                                    const Chunk *__restrict__ chunks, uint32_t nfull,
+                                                                    uint32_t nchunks, uint32_t span, StepScalars s,
+                                                                    const double *__restrict__ sums, WorkQueue *__restrict__ q,
+                                                                    const int32_t *__restrict__ flag)
+{
+    if (*flag != 0) return;
+    typedef LambPhase2Op<EMIT16> Op;
+    Op a, b;
+    auto bind = [&](Op &op, uint32_t entry) {
+        const Where wh = locate_at(tensors, chunks, entry, s.chunk_elems);
+        const double sw = sums[2 * (uint64_t)wh.tensor], su = sums[2 * (uint64_t)wh.tensor + 1];
+        const float ratio = (sw > 0.0 && su > 0.0) ? (float)(__builtin_sqrt(sw) / __builtin_sqrt(su)) : 1.0f;
+        op.init(wh.t, wh.base, s, ratio);
+        return wh;
+    };
+    ordered_stream<BLOCK, 2>(a, b, bind, nfull, nchunks, span, q);
+    leave_queue<false>(false, q, nullptr);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -656,6 +898,7 @@ struct ReduceOp {
         bad |= not_finite(S);
         st_f32(gsum, j * 4, S);
     }
+    template <int BLOCK> __device__ __forceinline__ void end_chunk(uint32_t) {}
 };
 
 template <int R, int BLOCK, bool GF32 = false>
@@ -668,6 +911,23 @@ __global__ __launch_bounds__(BLOCK) void reduce_kernel(const DevTensor *__restri
     op.init(wh.t, wh.base);
     stream_chunk<BLOCK>(op, wh.len);
     publish_flag<BLOCK>(op.bad, fs, flag);
+}
+
+template <int R, int BLOCK, bool GF32 = false>
+__global__ __launch_bounds__(BLOCK) void reduce_ordered_kernel(const DevTensor *__restrict__ tensors,
+                                                               const Chunk *__restrict__ chunks, uint32_t nfull,
+                                                               uint32_t nchunks, uint32_t span, StepScalars s, WorkQueue *__restrict__ q,
+                                                               int32_t *__restrict__ flag)
+{
+    typedef ReduceOp<R, GF32> Op;
+    Op a, b;
+    auto bind = [&](Op &op, uint32_t entry) {
+        const Where wh = locate_at(tensors, chunks, entry, s.chunk_elems);
+        op.init(wh.t, wh.base);
+        return wh;
+    };
+    ordered_stream<BLOCK, 2>(a, b, bind, nfull, nchunks, span, q);
+    leave_queue<true>(a.bad | b.bad, q, flag);
 }
 
 // The reduce stage of the fp16 all-reduce baseline: the sum of the R fp16 slices leaves as fp16.  The slices are
@@ -710,6 +970,7 @@ struct ReduceHalfOp {
         for (int r = 1; r < R; ++r) S += (double)ld_f16(grad.g[r], j * 2);
         st_f16(gsum, j * 2, through_half(S, bad));
     }
+    template <int BLOCK> __device__ __forceinline__ void end_chunk(uint32_t) {}
 };
 
 template <int R, int BLOCK>
@@ -722,6 +983,23 @@ __global__ __launch_bounds__(BLOCK) void reduce_half_kernel(const DevTensor *__r
     op.init(wh.t, wh.base);
     stream_chunk<BLOCK>(op, wh.len);
     publish_flag<BLOCK>(op.bad, fs, flag);
+}
+
+template <int R, int BLOCK>
+__global__ __launch_bounds__(BLOCK) void reduce_half_ordered_kernel(const DevTensor *__restrict__ tensors,
+                                                                    const Chunk *__restrict__ chunks, uint32_t nfull,
+                                                                    uint32_t nchunks, uint32_t span, StepScalars s, WorkQueue *__restrict__ q,
+                                                                    int32_t *__restrict__ flag)
+{
+    typedef ReduceHalfOp<R> Op;
+    Op a, b;
+    auto bind = [&](Op &op, uint32_t entry) {
+        const Where wh = locate_at(tensors, chunks, entry, s.chunk_elems);
+        op.init(wh.t, wh.base);
+        return wh;
+    };
+    ordered_stream<BLOCK, 2>(a, b, bind, nfull, nchunks, span, q);
+    leave_queue<true>(a.bad | b.bad, q, flag);
 }
 
 struct CastOp {
@@ -738,6 +1016,7 @@ struct CastOp {
     __device__ __forceinline__ void compute(Regs &) {}
     __device__ __forceinline__ void store(const Regs &x, uint32_t e) const { st_f16x4(w16, e * 2, x.w); }
     __device__ __forceinline__ void single(uint32_t j) { st_f16(w16, j * 2, ld_f32(w_new, j * 4)); }
+    template <int BLOCK> __device__ __forceinline__ void end_chunk(uint32_t) {}
 };
 
 // fp32 master weights -> fp16 copy.  `guarded`: leave w16 alone on overflow (whole-step skip).
@@ -751,6 +1030,23 @@ __global__ __launch_bounds__(BLOCK) void cast_kernel(const DevTensor *__restrict
     CastOp op;
     op.init(wh.t, wh.base);
     stream_chunk<BLOCK>(op, wh.len);
+}
+
+template <int BLOCK>
+__global__ __launch_bounds__(BLOCK) void cast_ordered_kernel(const DevTensor *__restrict__ tensors,
+                                                             const Chunk *__restrict__ chunks, uint32_t nfull,
+                                                             uint32_t nchunks, uint32_t span, StepScalars s, WorkQueue *__restrict__ q,
+                                                             const int32_t *__restrict__ flag, int guarded)
+{
+    if (guarded && *flag != 0) return;
+    CastOp a, b;
+    auto bind = [&](CastOp &op, uint32_t entry) {
+        const Where wh = locate_at(tensors, chunks, entry, s.chunk_elems);
+        op.init(wh.t, wh.base);
+        return wh;
+    };
+    ordered_stream<BLOCK, 2>(a, b, bind, nfull, nchunks, span, q);
+    leave_queue<false>(false, q, nullptr);
 }
 
 // ---------------------------------------------------------------------------------------------------

@@ -19,11 +19,12 @@ from .workloads import aligned_offsets
 class Shard:
     def __init__(self, numels: Sequence[int], weight_decays: Sequence[float], R: int, device="cuda",
                  chunk_elems: int = 0, in_place: bool = False, align_elems: int = 4096, skew_elems: int = 0,
-                 grad_dtype: torch.dtype = torch.float16):
+                 grad_dtype: torch.dtype = torch.float16, schedule: int = cc.CC_SCHEDULE_AUTO, workgroups: int = 0):
         """align_elems: tensor starts are multiples of this many elements (>= 8 keeps them 16-byte aligned
         in the fp16 arenas).  The default places every tensor on a chunk boundary (4096 elements = 16 KiB of
         fp32), which measures ~5 % faster than 256-byte alignment: a chunk then covers whole DRAM interleave
-        units instead of straddling them.  skew_elems shifts the whole arena start (multiple of 8)."""
+        units instead of straddling them.  skew_elems shifts the whole arena start (multiple of 8).
+        schedule / workgroups: passed to cc_plan_set_schedule for both plans (AUTO leaves the library's choice)."""
         assert align_elems % 8 == 0 and skew_elems % 8 == 0
         self.numels = list(numels)
         self.wds = list(weight_decays)
@@ -60,6 +61,8 @@ class Shard:
                     for k, nk in enumerate(self.numels)]
             self.plans.append(cc.cc_plan_create_ex(tens, R, chunk_elems,
                                                    cc.CC_GRAD_F16 if grad_dtype == torch.float16 else cc.CC_GRAD_F32))
+            if schedule != cc.CC_SCHEDULE_AUTO or workgroups:
+                cc.cc_plan_set_schedule(self.plans[-1], schedule, workgroups)
 
     def _addr(self, arena: torch.Tensor, k: int, itemsize: int) -> int:
         return arena.data_ptr() + (self.skew + self.offsets[k]) * itemsize

@@ -2,8 +2,9 @@
 standalone experiment, Section 6.1.1 / Fig. 7), with the launch shape tuned per size.
 
 For every size and every path (fused Adam, unfused Adam, fused LAMB, unfused LAMB) the step is timed for each
-candidate chunk size and the best average is kept, like the paper's autotuner keeps the best configuration per
-size.  Steps are replayed from a HIP graph so that small sizes measure the GPU, not the Python caller.
+candidate launch shape (one workgroup per chunk of 1024 / 4096 / 16384 elements, or the ordered persistent
+schedule on 4096-element chunks) and the best average is kept, like the paper's autotuner keeps the best
+configuration per size.  Steps are replayed from a HIP graph so that small sizes measure the GPU, not the Python caller.
 
     python -m paper_2105_05720_amd.size_sweep [--min-log2 10] [--max-log2 30] [--R 8] [--markdown out.md]
 """
@@ -18,7 +19,8 @@ import torch
 from . import binding as cc
 from .shard import Shard
 
-CHUNKS = (1024, 4096, 16384)
+PC, ORD = cc.CC_SCHEDULE_PER_CHUNK, cc.CC_SCHEDULE_ORDERED
+SHAPES = ((1024, PC), (4096, PC), (16384, PC), (4096, ORD))       # (chunk elements, schedule)
 PATHS = (("fused_adam", cc.cc_fused_adam_step, lambda R: 2 * R + 26),
          ("unfused_adam", cc.cc_unfused_adam_step, lambda R: 2 * R + 38),
          ("fused_lamb", cc.cc_fused_lamb_step, lambda R: 2 * R + 38),
@@ -68,10 +70,12 @@ def main() -> int:
         row = {"log2": k, "n": n}
         for name, fn, bpp in PATHS:
             best = None
-            for chunk in CHUNKS:
+            for chunk, sched in SHAPES:
                 if chunk > 1024 and n < chunk:          # one partial chunk either way
                     continue
-                shard = Shard([n], [0.01], R, chunk_elems=chunk)
+                if sched == ORD and n < 2 * chunk:
+                    continue
+                shard = Shard([n], [0.01], R, chunk_elems=chunk, schedule=sched)
                 g = torch.Generator(device="cuda")
                 g.manual_seed(k)
                 shard.w[0].normal_(0.0, 0.02, generator=g)
@@ -80,8 +84,11 @@ def main() -> int:
                 us = time_path(shard, fn, steps, per_graph)
                 shard.destroy()
                 del shard
+                tag = "%d%s" % (chunk, " ordered" if sched == ORD else "")
                 if best is None or us < best[0]:
-                    best = (us, chunk)
+                    best = (us, tag)
+                if sched == ORD:
+                    row.setdefault("ordered_us", {})[name] = round(us, 3)
             row[name] = {"us": round(best[0], 3), "chunk": best[1], "GB/s": round(bpp(R) * n / best[0] / 1e3, 1)}
         row["adam_fused_over_unfused"] = round(row["unfused_adam"]["us"] / row["fused_adam"]["us"], 3)
         row["lamb_fused_over_unfused"] = round(row["unfused_lamb"]["us"] / row["fused_lamb"]["us"], 3)
@@ -93,7 +100,7 @@ def main() -> int:
             f.write("| log2 N | fused Adam us (chunk) | GB/s | unfused Adam us | fused/unfused speed-up | fused LAMB us (chunk) | GB/s | unfused LAMB us | speed-up |\n")
             f.write("|---|---|---|---|---|---|---|---|---|\n")
             for r in rows:
-                f.write("| %d | %.2f (%d) | %.0f | %.2f | %.2fx | %.2f (%d) | %.0f | %.2f | %.2fx |\n" % (
+                f.write("| %d | %.2f (%s) | %.0f | %.2f | %.2fx | %.2f (%s) | %.0f | %.2f | %.2fx |\n" % (
                     r["log2"], r["fused_adam"]["us"], r["fused_adam"]["chunk"], r["fused_adam"]["GB/s"], r["unfused_adam"]["us"],
                     r["adam_fused_over_unfused"], r["fused_lamb"]["us"], r["fused_lamb"]["chunk"], r["fused_lamb"]["GB/s"],
                     r["unfused_lamb"]["us"], r["lamb_fused_over_unfused"]))
