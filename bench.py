@@ -24,8 +24,8 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 
 # HBM bytes per launch of the headline kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by what
-# the same counter reads for the plain copy kernel: default chunk size, fp16 slices, scattered list only.
-MEASURED_TRAFFIC_BYTES = {2: 9.4258e9 + 4.7096e9, 3: 1.3473e10 + 4.7122e9}     # profiles/fused_adam_config2.md, fused_lamb_config3.md
+# the same counter reads for the plain copy kernel: default chunk size and schedule, fp16 slices, scattered list only.
+MEASURED_TRAFFIC_BYTES = {2: 9.4490e9 + 4.7098e9, 3: 1.3499e10 + 4.7131e9}     # profiles/fused_adam_config2.md, fused_lamb_config3.md
 
 
 GRAD_BYTES = 2                 # bytes per gradient element (set to 4 by --grad-dtype f32)
@@ -188,7 +188,8 @@ def main() -> int:
         "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(gbs / HBM_PEAK_GBS, 4),
                      "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.index) if (args.chunk_elems == 0 and not args.in_place and not args.flat
-                                                                         and args.grad_dtype == "f16") else None,
+                                                                         and args.grad_dtype == "f16" and args.schedule == "auto"
+                                                                         and args.workgroups == 0) else None,
                      "kernel": ("fused_adam%s_kernel<R=%d>" % ("_ordered" if ordered else "", R)) if cfg.optimizer == "adam"
                      else "lamb_phase1%s_kernel + lamb_phase2%s_kernel" % (("_ordered",) * 2 if ordered else ("", "")),
                      "bytes_per_launch": bpp * N, "avg_launch_ms": round(ms, 5)},

@@ -70,6 +70,7 @@ struct cc_plan {
     int32_t schedule = CC_SCHEDULE_AUTO;    // what the caller asked for
     unsigned ordered_grid = 0;              // workgroups of the ordered schedule (one per compute unit unless set)
     int32_t cus = 0;                        // compute units of the device the plan was created on
+    int32_t single = -1;                    // index of the only tensor with elements, or -1 if there are several (or none)
     uint32_t nfull = 0;                     // full chunks; the ordered table lists them first, short last chunks behind
     Chunk *d_chunks_ordered = nullptr;
     WorkQueue *d_queue = nullptr;           // zero between launches
@@ -227,6 +228,12 @@ int cc_plan_create_ex(const cc_tensor *tensors, int32_t T, int32_t R, int32_t ch
     }
     p->numel = total;
     p->gsum_elems = goff;
+    {
+        int32_t nonempty = 0;
+        for (int32_t t = 0; t < T; ++t)
+            if (tensors[t].numel > 0) { ++nonempty; p->single = t; }
+        if (nonempty != 1) p->single = -1;
+    }
     cc_chunk_table_fill(numels.data(), T, ce, table.data(), chunks);
     // The ordered schedule's table: the same entries, full chunks first (tensor order = address order inside each
     // arena), then the short last chunks, which take the unpipelined path.
@@ -437,6 +444,15 @@ void launch_fused_adam_r(const cc_plan *p, const StepScalars &s, int32_t *flag, 
         return;
     }
     const dim3 grid((unsigned)p->chunks), block(BLK);
+    if (p->single >= 0) {                  // one tensor: no table, descriptor in the kernel arguments
+        const DevTensor &t = p->host_tensors[(size_t)p->single];
+        switch (p->R) {
+#define CASE(r) case r: hipLaunchKernelGGL((fused_adam_flat_kernel<r, MODE, BLK, GF32>), grid, block, 0, st, t, s, p->d_flag_scratch, flag); break;
+            FOR_EACH_R(CASE)
+#undef CASE
+        }
+        return;
+    }
     switch (p->R) {
 #define CASE(r) case r: hipLaunchKernelGGL((fused_adam_kernel<r, MODE, BLK, GF32>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, p->d_flag_scratch, flag); break;
         FOR_EACH_R(CASE)

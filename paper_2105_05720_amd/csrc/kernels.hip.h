@@ -88,7 +88,10 @@ __device__ __forceinline__ float direction(float w, float wd, float m, float v, 
 {
     const float mh = m * s.rc1;
     const float vh = v * s.rc2;
-    float u = mh / (__builtin_sqrtf(vh) + s.eps);
+    // v_sqrt_f32 and v_rcp_f32, each within 1 ulp: the quotient is off by at most ~3 x 2^-24 relative, which moves
+    // w by lr |u| 2e-7, two orders below the 2e-6 parity bound; the IEEE sequences cost 20 more instructions per
+    // element, which a small (launch-bound) shard pays in full.
+    float u = mh * __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(vh) + s.eps);
     if (!(MODE & kModeL2)) u = __builtin_fmaf(wd, w, u);
     return u;
 }
@@ -176,16 +179,29 @@ struct FlagScratch {
     struct alignas(128) Line { unsigned long long word; } slot[kFlagSlots], top;
 };
 
+// The count is taken in two steps so that the first atomic's round trip can pass under the workgroup's arithmetic:
+// publish_begin (after the sums, which decide `bad`) issues it, publish_end (after the stores) looks at what came back.
+struct FlagTicket { unsigned long long mine, prev; };
+
 template <int BLOCK>
-__device__ __forceinline__ void publish_flag(bool bad, FlagScratch *fs, int32_t *flag)
+__device__ __forceinline__ FlagTicket publish_begin(bool bad, FlagScratch *fs)
 {
     const int any = BLOCK > 64 ? __syncthreads_or(bad ? 1 : 0) : (__builtin_amdgcn_ballot_w64(bad) != 0ull ? 1 : 0);
+    FlagTicket t;
+    t.mine = 1ull | (any ? (1ull << 32) : 0ull);
+    t.prev = 0ull;
+    if (threadIdx.x == 0)
+        t.prev = atomicAdd(gridDim.x <= kFlagSlots ? &fs->top.word : &fs->slot[blockIdx.x % kFlagSlots].word, t.mine);
+    return t;
+}
+
+__device__ __forceinline__ void publish_end(const FlagTicket &t, FlagScratch *fs, int32_t *flag)
+{
     if (threadIdx.x == 0) {
-        const unsigned long long mine0 = 1ull | (any ? (1ull << 32) : 0ull);
-        if (gridDim.x <= kFlagSlots) {                  // few workgroups: count on the top word directly
-            const unsigned long long tprev = atomicAdd(&fs->top.word, mine0);
-            if ((uint32_t)tprev == gridDim.x - 1) {
-                *flag = ((tprev + mine0) >> 32) != 0ull ? 1 : 0;
+        const unsigned long long mine = t.mine, prev = t.prev;
+        if (gridDim.x <= kFlagSlots) {                  // few workgroups: counted on the top word directly
+            if ((uint32_t)prev == gridDim.x - 1) {
+                *flag = ((prev + mine) >> 32) != 0ull ? 1 : 0;
                 atomicExch(&fs->top.word, 0ull);
             }
             return;
@@ -193,8 +209,6 @@ __device__ __forceinline__ void publish_flag(bool bad, FlagScratch *fs, int32_t 
         const uint32_t slot = blockIdx.x % kFlagSlots;
         const uint32_t in_slot = (gridDim.x - slot + kFlagSlots - 1) / kFlagSlots;      // workgroups b with b % 64 == slot
         const uint32_t slots_used = gridDim.x < kFlagSlots ? gridDim.x : kFlagSlots;
-        const unsigned long long mine = 1ull | (any ? (1ull << 32) : 0ull);
-        const unsigned long long prev = atomicAdd(&fs->slot[slot].word, mine);
         if ((uint32_t)prev == in_slot - 1) {            // this workgroup completed its slot
             atomicExch(&fs->slot[slot].word, 0ull);
             const unsigned long long up = 1ull | (((prev + mine) >> 32) != 0ull ? (1ull << 32) : 0ull);
@@ -205,6 +219,12 @@ __device__ __forceinline__ void publish_flag(bool bad, FlagScratch *fs, int32_t 
             }
         }
     }
+}
+
+template <int BLOCK>
+__device__ __forceinline__ void publish_flag(bool bad, FlagScratch *fs, int32_t *flag)
+{
+    publish_end(publish_begin<BLOCK>(bad, fs), fs, flag);
 }
 
 // Only for a plan without any chunk: nothing else would write the flag.
@@ -248,6 +268,34 @@ __device__ __forceinline__ void stream_chunk(Op &op, uint32_t len)
         } else {
             for (uint32_t j = e; j < len; ++j) op.single(j);
         }
+    }
+}
+
+// One workgroup per chunk, for an Op that raises the flag and splits compute into reduce + update: when the chunk
+// is exactly one sweep (the launch shapes the plans use), the count for the flag is started as soon as the sums
+// are known, so that the atomic's latency passes under the update arithmetic instead of behind the stores.  That
+// is worth ~0.5 us on a shard that is one wave of workgroups deep.
+template <int BLOCK, int GROUPS, class Op>
+__device__ __forceinline__ void sweep_and_publish(Op &op, uint32_t len, FlagScratch *fs, int32_t *flag)
+{
+    constexpr uint32_t kGroup = BLOCK * Op::kPack;
+    if (len == GROUPS * kGroup) {
+        const uint32_t lane_e = threadIdx.x * Op::kPack;
+        typename Op::Regs x[GROUPS];
+#pragma unroll
+        for (int g = 0; g < GROUPS; ++g) op.load(x[g], g * kGroup + lane_e);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int g = 0; g < GROUPS; ++g) op.reduce(x[g]);
+        const FlagTicket t = publish_begin<BLOCK>(op.bad, fs);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int g = 0; g < GROUPS; ++g) { op.update(x[g]); op.store(x[g], g * kGroup + lane_e); }
+        __builtin_amdgcn_sched_barrier(0);
+        publish_end(t, fs, flag);
+    } else {
+        stream_chunk<BLOCK, Op, GROUPS>(op, len);
+        publish_flag<BLOCK>(op.bad, fs, flag);
     }
 }
 
@@ -478,7 +526,7 @@ struct AdamOp {
     StepScalars s;
     float wd;
     bool bad = false;
-    struct Regs { typename Grad::Regs g; float w[4], m[4], v[4]; };
+    struct Regs { typename Grad::Regs g; float S[4], w[4], m[4], v[4]; };
 
     __device__ __forceinline__ void init(const DevTensor *t, uint64_t base, const StepScalars &sc)
     {
@@ -505,12 +553,21 @@ struct AdamOp {
         const float wk = __builtin_fmaf(-s.lr, direction<MODE>(w, wd, mk, vk, s), w);
         if (!(MODE & kModeGuard) || !nf) { m = mk; v = vk; w = wk; }
     }
+    // compute = reduce (the sums, which settle `bad`) + update (everything else)
+    __device__ __forceinline__ void reduce(Regs &x)
+    {
+        grad.sum(x.g, x.S);
+        bad = bad || not_finite(x.S[0]) || not_finite(x.S[1]) || not_finite(x.S[2]) || not_finite(x.S[3]);
+    }
+    __device__ __forceinline__ void update(Regs &x)
+    {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) one(x.S[k], x.w[k], x.m[k], x.v[k]);
+    }
     __device__ __forceinline__ void compute(Regs &x)
     {
-        float S[4];
-        grad.sum(x.g, S);
-#pragma unroll
-        for (int k = 0; k < 4; ++k) one(S[k], x.w[k], x.m[k], x.v[k]);
+        reduce(x);
+        update(x);
     }
     __device__ __forceinline__ void store(const Regs &x, uint32_t e) const
     {
@@ -535,8 +592,22 @@ __global__ __launch_bounds__(BLOCK) void fused_adam_kernel(const DevTensor *__re
     const Where wh = locate(tensors, chunks, s.chunk_elems);
     AdamOp<GradSlices<R, GF32>, MODE, true> op;
     op.init(wh.t, wh.base, s);
-    stream_chunk<BLOCK, decltype(op), GROUPS>(op, wh.len);
-    publish_flag<BLOCK>(op.bad, fs, flag);
+    sweep_and_publish<BLOCK, GROUPS>(op, wh.len, fs, flag);
+}
+
+// A plan with a single tensor (the contiguous case of Table 2 and of the standalone sweep of Section 6.1.1) needs
+// no table: workgroup b takes chunk b, and the descriptor travels in the kernel arguments, so the two dependent
+// scalar loads (table entry, then descriptor) in front of the first vector load fall away.  ~1 us of a launch-bound
+// step.
+template <int R, int MODE, int BLOCK, bool GF32 = false, int GROUPS = 2>
+__global__ __launch_bounds__(BLOCK) void fused_adam_flat_kernel(DevTensor t, StepScalars s, FlagScratch *__restrict__ fs,
+                                                                int32_t *__restrict__ flag)
+{
+    const uint64_t base = (uint64_t)blockIdx.x * s.chunk_elems;
+    const uint64_t rem = t.numel - base;
+    AdamOp<GradSlices<R, GF32>, MODE, true> op;
+    op.init(&t, base, s);
+    sweep_and_publish<BLOCK, GROUPS>(op, rem < s.chunk_elems ? (uint32_t)rem : s.chunk_elems, fs, flag);
 }
 
 // The same step under the ordered persistent schedule (chunk_elems == BLOCK * 4 * GROUPS).
@@ -632,7 +703,7 @@ struct LambPhase1Op {
     bool bad = false;
     float sw = 0.f, su = 0.f;        // per lane: at most chunk_elems / BLOCK terms each, then double
     double *partials = nullptr;      // 2 per chunk, indexed by the chunk's position in tensor order
-    struct Regs { typename Grad::Regs g; float w[4], m[4], v[4]; };
+    struct Regs { typename Grad::Regs g; float S[4], w[4], m[4], v[4]; };
 
     __device__ __forceinline__ void init(const DevTensor *t, uint64_t base, const StepScalars &sc)
     {
@@ -656,12 +727,20 @@ struct LambPhase1Op {
         sw = __builtin_fmaf(w, w, sw);
         su = __builtin_fmaf(u, u, su);
     }
+    __device__ __forceinline__ void reduce(Regs &x)
+    {
+        grad.sum(x.g, x.S);
+        bad = bad || not_finite(x.S[0]) || not_finite(x.S[1]) || not_finite(x.S[2]) || not_finite(x.S[3]);
+    }
+    __device__ __forceinline__ void update(Regs &x)
+    {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) one(x.S[k], x.w[k], x.m[k], x.v[k]);
+    }
     __device__ __forceinline__ void compute(Regs &x)
     {
-        float S[4];
-        grad.sum(x.g, S);
-#pragma unroll
-        for (int k = 0; k < 4; ++k) one(S[k], x.w[k], x.m[k], x.v[k]);
+        reduce(x);
+        update(x);
     }
     __device__ __forceinline__ void store(const Regs &x, uint32_t e) const
     {
@@ -696,9 +775,12 @@ __device__ __forceinline__ void lamb_phase1_body(const DevTensor *__restrict__ t
     LambPhase1Op<Grad> op;
     op.init(wh.t, wh.base, s);
     op.partials = partials;
-    stream_chunk<BLOCK>(op, wh.len);
+    if (RAISE) {
+        sweep_and_publish<BLOCK, 2>(op, wh.len, fs, flag);
+    } else {
+        stream_chunk<BLOCK>(op, wh.len);
+    }
     op.template end_chunk<BLOCK>(wh.slot);
-    if (RAISE) publish_flag<BLOCK>(op.bad, fs, flag);
 }
 
 template <class Grad, bool RAISE, int BLOCK>
