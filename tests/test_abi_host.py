@@ -142,6 +142,9 @@ def test_step_calls_reject_null_plan_and_bad_copy_arguments():
     assert lib.cc_copy_probe(0x1000, 0x2000, 17, None) == cc.CC_ERR_ARG
     assert lib.cc_copy_probe(0x1008, 0x2000, 32, None) == cc.CC_ERR_ALIGN
     assert lib.cc_plan_destroy(None) == cc.CC_OK
+    assert lib.cc_plan_set_schedule(None, cc.CC_SCHEDULE_ORDERED, 0) == cc.CC_ERR_NULL
+    assert lib.cc_plan_schedule(None, None, None) == cc.CC_ERR_NULL
+    assert "plan is NULL" in cc.cc_last_error()
 
 
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):

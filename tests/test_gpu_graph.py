@@ -19,11 +19,15 @@ def _bits(shard):
             shard.w16[c].view(torch.int16).clone(), shard.flag.clone()]
 
 
-@pytest.mark.parametrize("fn", [cc.cc_fused_adam_step, cc.cc_fused_lamb_step])
-def test_graph_replays_match_eager(fn):
+@pytest.mark.parametrize("schedule", [cc.CC_SCHEDULE_AUTO, cc.CC_SCHEDULE_ORDERED])
+@pytest.mark.parametrize("fn", [cc.cc_fused_adam_step, cc.cc_fused_lamb_step, cc.cc_unfused_adam_step])
+def test_graph_replays_match_eager(fn, schedule):
+    """AUTO gives these small lists one workgroup per chunk; ORDERED forces the persistent schedule, whose work
+    queue is handed back zeroed by the kernel itself (no memset node), with 7 workgroups for 82 chunks."""
     numels, wds, R = [20000, 4097, 3, 300000], [0.01, 0.0, 0.01, 0.01], 4
-    eager = Shard(numels, wds, R, align_elems=8)
-    graphed = Shard(numels, wds, R, align_elems=8)
+    kw = dict(chunk_elems=4096, schedule=schedule, workgroups=7) if schedule == cc.CC_SCHEDULE_ORDERED else {}
+    eager = Shard(numels, wds, R, align_elems=8, **kw)
+    graphed = Shard(numels, wds, R, align_elems=8, **kw)
     for s in (eager, graphed):
         seeded_state(s, 21)
         seeded_grads(s, 210, 1e-2)

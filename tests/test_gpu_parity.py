@@ -436,3 +436,32 @@ def test_fp16_intermediate_overflows_where_the_fused_sum_does_not():
         _unfused_f16(plan_f32.plans[0], cc.Hyper(), plan_f32.flag)
     assert e.value.code == cc.CC_ERR_ARG
     plan_f32.destroy()
+
+
+# ---- plans with one tensor: no table, descriptor in the kernel arguments ----
+
+@pytest.mark.parametrize("numels", [[0, 5000, 0], [1], [1024], [1025], [4096 * 3], [4096 * 3 + 7], [0, 0, 20481]])
+@pytest.mark.parametrize("chunk", [0, 4096])
+def test_adam_single_tensor_plans(numels, chunk):
+    adam_case(numels, 3, steps=2, chunk=chunk, label="adam single tensor %s chunk=%d" % (numels, chunk))
+
+
+@pytest.mark.parametrize("kw", [dict(skip_mode=1), dict(adam_mode=0, grad_average=1)])
+def test_adam_single_tensor_modes_and_fp32_gradients(kw):
+    adam_case([0, 12289], 5, steps=2, label="adam single tensor %s" % kw, **kw)
+    adam_case([12289], 2, steps=1, grad_dtype=torch.float32, label="adam single tensor fp32 %s" % kw, **kw)
+
+
+def test_adam_single_tensor_overflow_skip():
+    numels = [0, 9000]
+    shard = Shard(numels, [0.0, 0.01], 4, align_elems=8)
+    seeded_state(shard, 8)
+    ost = OracleState(shard, range(2))
+
+    def fill(i):
+        seeded_grads(shard, 80 + i, 1e-2)
+        if i == 1:
+            _inject(shard, 3, 1, 8999, 0xFC00)
+    hps = [hyper_pair(step=1), hyper_pair(step=2), hyper_pair(step=2)]
+    run_steps(shard, ost, cc.cc_fused_adam_step, oracle.adam_step, hps, "adam single tensor skip", fill, expect_flags=[0, 1, 0])
+    shard.destroy()
