@@ -21,7 +21,7 @@ constexpr int32_t kSmallChunkElems = 1024;       // one sweep of a 128-thread wo
 constexpr uint64_t kSmallShardElems = 64u << 20; // below this many elements the default chunk is the small one (size sweep)
 constexpr int32_t kMaxChunkElems = 1 << 24;      // lane offsets inside a chunk are 32-bit byte offsets
 constexpr int kBigBlock = 512, kSmallBlock = 128;
-constexpr int kOrderedMaxF32Slices = 8;           // two chunks of more fp32 slices than this do not fit the register file
+constexpr int kOrderedMaxF32Slices = 4;           // fp32 slices: measured faster up to 4, slower at 8 (two chunks of 8 take 209 VGPRs)
 constexpr int64_t kOrderedMinChunksPerCu = 8;    // below this many chunks per compute unit a plan keeps one workgroup per chunk
 
 thread_local char g_err[512] = "";
