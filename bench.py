@@ -58,8 +58,9 @@ def main() -> int:
     ap.add_argument("--grad-dtype", choices=("f16", "f32"), default="f16", help="element type of the R gradient slices")
     ap.add_argument("--flat", action="store_true", help="the same number of parameters as ONE contiguous tensor (Table 2's single-tensor case)")
     ap.add_argument("--graph", action="store_true", help="enqueue the timed steps as replays of a captured HIP graph of 20 steps")
-    ap.add_argument("--schedule", choices=("auto", "per-chunk", "ordered"), default="auto",
-                    help="how the kernels are laid over the device (cc_plan_set_schedule); auto = the library's choice")
+    ap.add_argument("--schedule", choices=("auto", "per-chunk", "ordered", "tuned"), default="auto",
+                    help="how the kernels are laid over the device (cc_plan_set_schedule); auto = the library's size rule, "
+                         "tuned = cc_plan_autotune measures the candidates on this workload first")
     ap.add_argument("--workgroups", type=int, default=0, help="workgroups of the ordered schedule (0 = one per compute unit)")
     ap.add_argument("--no-extras", action="store_true", help="only the headline step (for profiling runs)")
     ap.add_argument("--copy-only", action="store_true", help="run only the plain copy kernel (2 GiB, 20 launches): counter calibration")
@@ -104,13 +105,19 @@ def main() -> int:
     shard = Shard([s.numel for s in cfg.params], [cfg.wd_of(s) for s in cfg.params], R, device=dev,
                   chunk_elems=args.chunk_elems, in_place=args.in_place,
                   grad_dtype=torch.float16 if args.grad_dtype == "f16" else torch.float32,
-                  schedule={"auto": cc.CC_SCHEDULE_AUTO, "per-chunk": cc.CC_SCHEDULE_PER_CHUNK, "ordered": cc.CC_SCHEDULE_ORDERED}[args.schedule],
+                  schedule={"auto": cc.CC_SCHEDULE_AUTO, "per-chunk": cc.CC_SCHEDULE_PER_CHUNK, "ordered": cc.CC_SCHEDULE_ORDERED,
+                            "tuned": cc.CC_SCHEDULE_AUTO}[args.schedule],
                   workgroups=args.workgroups)
-    sched, wgs = cc.cc_plan_schedule(shard.plans[0])
-    ordered = sched == cc.CC_SCHEDULE_ORDERED
     W.fill_state(shard, cfg)
     W.fill_grads(shard, cfg, 1)
     torch.cuda.synchronize()
+    tuned = None
+    if args.schedule == "tuned":
+        assert not args.in_place, "--schedule tuned needs out-of-place state"
+        hp1 = cc.Hyper(lr=cfg.lr, beta1=cfg.beta1, beta2=cfg.beta2, eps=cfg.eps, loss_scale=cfg.loss_scale, step=1)
+        tuned = [cc.cc_plan_autotune(p, hp1, shard.flag, 0 if cfg.optimizer == "adam" else 1) for p in shard.plans]
+    sched, wgs = cc.cc_plan_schedule(shard.plans[0])
+    ordered = sched == cc.CC_SCHEDULE_ORDERED
     _, chunks, table_bytes = cc.cc_plan_info(shard.plans[0])
     skip_mode = 1 if args.in_place else 0
 
@@ -184,6 +191,7 @@ def main() -> int:
                    "chunks": chunks, "launch": "hip graph replay" if args.graph else "eager",
                    "schedule": ("ordered: %d persistent workgroups take the chunks in table order" % wgs) if ordered
                    else "one workgroup per chunk",
+                   "autotune_ms_best_and_per_chunk": [round(x, 5) for x in tuned[0]] if tuned else None,
                    "table_bytes": table_bytes, "algorithmic_bytes_per_param": bpp},
         "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(gbs / HBM_PEAK_GBS, 4),

@@ -139,6 +139,19 @@ typedef enum cc_schedule { CC_SCHEDULE_AUTO = 0, CC_SCHEDULE_PER_CHUNK = 1, CC_S
 int cc_plan_set_schedule(cc_plan *plan, int32_t schedule, int32_t workgroups);
 int cc_plan_schedule(const cc_plan *plan, int32_t *schedule, int32_t *workgroups);
 
+/*
+ * Picks the schedule by measurement instead of by the size rule, as the paper's autotuner keeps the fastest
+ * configuration per workload (Section 5.3): runs the plan's own fused step (optimizer 0 = Adam, 1 = LAMB) a few
+ * times under each candidate (one workgroup per chunk; ordered with compute units / 2, x 1 and x 2 workgroups, if the
+ * plan's chunk size allows it), timed with events on `hip_stream`, and leaves the plan set to the fastest.  The
+ * trial steps are ordinary steps on the caller's buffers: they write the out buffers and the flag, never the in
+ * buffers, so the plan must be out of place (CC_ERR_ALIAS otherwise) and the caller must not have adopted the out
+ * buffers' contents.  Synchronises the stream.  best_ms / per_chunk_ms (each may be NULL) receive the time per step
+ * of the schedule kept and of one workgroup per chunk.
+ */
+int cc_plan_autotune(cc_plan *plan, const cc_hparams *hp, int32_t optimizer, int32_t *d_overflow_flag,
+                     void *hip_stream, float *best_ms, float *per_chunk_ms);
+
 /* Totals of a plan: elements, chunks and bytes of table memory on the device. */
 int cc_plan_info(const cc_plan *plan, uint64_t *numel, int64_t *chunks, uint64_t *table_bytes);
 

@@ -57,6 +57,8 @@ EXPORTS = {
     "cc_plan_destroy": (C.c_int, [C.c_void_p]),
     "cc_plan_set_schedule": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32]),
     "cc_plan_schedule": (C.c_int, [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
+    "cc_plan_autotune": (C.c_int, [C.c_void_p, C.POINTER(cc_hparams), C.c_int32, C.c_void_p, C.c_void_p,
+                                   C.POINTER(C.c_float), C.POINTER(C.c_float)]),
     "cc_plan_info": (C.c_int, [C.c_void_p, C.POINTER(C.c_uint64), C.POINTER(C.c_int64), C.POINTER(C.c_uint64)]),
     "cc_fused_adam_step": (C.c_int, [C.c_void_p, C.POINTER(cc_hparams), C.c_void_p, C.c_void_p]),
     "cc_fused_lamb_step": (C.c_int, [C.c_void_p, C.POINTER(cc_hparams), C.c_void_p, C.c_void_p]),
@@ -225,6 +227,15 @@ def cc_plan_schedule(plan: Plan):
     sched, wgs = C.c_int32(), C.c_int32()
     _check(load().cc_plan_schedule(plan.handle, C.byref(sched), C.byref(wgs)))
     return sched.value, wgs.value
+
+
+def cc_plan_autotune(plan: Plan, hp, flag, optimizer: int = 0, stream=None):
+    """Times the candidate schedules on the plan's own buffers and keeps the fastest.  Returns (ms per step of the
+    schedule kept, ms per step with one workgroup per chunk)."""
+    c = _hp(hp)
+    best, per_chunk = C.c_float(), C.c_float()
+    _check(load().cc_plan_autotune(plan.handle, C.byref(c), optimizer, _ptr(flag), _stream(stream), C.byref(best), C.byref(per_chunk)))
+    return best.value, per_chunk.value
 
 
 def cc_plan_info(plan: Plan):

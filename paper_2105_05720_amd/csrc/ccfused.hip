@@ -786,6 +786,61 @@ int cc_unfused_epilogue(const cc_epilogue *e, float *d_sum, void *stream)
     return launched("epilogue_pointwise_kernel");
 }
 
+int cc_plan_autotune(cc_plan *p, const cc_hparams *hp, int32_t optimizer, int32_t *flag, void *stream, float *best_ms,
+                     float *per_chunk_ms)
+{
+    if (!p) return fail(CC_ERR_NULL, "cc_plan_autotune: plan is NULL");
+    if (optimizer != 0 && optimizer != 1) return fail(CC_ERR_ARG, "cc_plan_autotune: optimizer = %d", optimizer);
+    if (p->in_place) return fail(CC_ERR_ALIAS, "cc_plan_autotune needs out buffers distinct from the in buffers");
+    {
+        StepScalars s;
+        const int rc = check_step(p, hp, flag, optimizer == 0 ? Opt::Adam : Opt::Lamb, &s);
+        if (rc) return rc;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    const int32_t keep_schedule = p->schedule;
+    const unsigned keep_grid = p->ordered_grid;
+    struct Candidate { int32_t schedule; unsigned workgroups; };
+    Candidate cand[4] = {{CC_SCHEDULE_PER_CHUNK, 0u}, {0, 0u}, {0, 0u}, {0, 0u}};
+    int n = 1;
+    if (p->chunk_elems == kDefaultChunkElems && p->chunks > 0) {
+        const unsigned cus = (unsigned)p->cus;
+        const unsigned tries[3] = {cus, cus > 1 ? cus / 2 : 1u, cus * 2};
+        for (unsigned w : tries) cand[n++] = Candidate{CC_SCHEDULE_ORDERED, w};
+    }
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    HIP_TRY(hipEventCreate(&e0));
+    if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return fail(CC_ERR_HIP, "hipEventCreate failed"); }
+    auto restore = [&](int32_t schedule, unsigned grid) { p->schedule = schedule; p->ordered_grid = grid; resolve_schedule(p); };
+    int rc = CC_OK, best = -1;
+    float best_time = 0.f;
+    constexpr int kTrials = 3;
+    for (int c = 0; c < n && rc == CC_OK; ++c) {
+        restore(cand[c].schedule, cand[c].workgroups);
+        float ms = 0.f;
+        for (int i = 0; i <= kTrials && rc == CC_OK; ++i) {          // the first run warms up
+            if (i == 1 && hipEventRecord(e0, st) != hipSuccess) rc = fail(CC_ERR_HIP, "hipEventRecord failed");
+            if (rc == CC_OK) rc = optimizer == 0 ? cc_fused_adam_step(p, hp, flag, stream) : cc_fused_lamb_step(p, hp, flag, stream);
+        }
+        if (rc == CC_OK && (hipEventRecord(e1, st) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+                            hipEventElapsedTime(&ms, e0, e1) != hipSuccess))
+            rc = fail(CC_ERR_HIP, "timing a trial step failed");
+        if (rc != CC_OK) break;
+        ms /= (float)kTrials;
+        if (c == 0 && per_chunk_ms) *per_chunk_ms = ms;
+        if (best < 0 || ms < best_time) { best = c; best_time = ms; }
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (rc != CC_OK) {
+        restore(keep_schedule, keep_grid);
+        return rc;
+    }
+    restore(cand[best].schedule, cand[best].workgroups);
+    if (best_ms) *best_ms = best_time;
+    return CC_OK;
+}
+
 int cc_device_info(int32_t *cus, int32_t *clock_khz, int32_t *bus_bits, uint64_t *total_bytes)
 {
     int dev = 0, v = 0;

@@ -144,6 +144,7 @@ def test_step_calls_reject_null_plan_and_bad_copy_arguments():
     assert lib.cc_plan_destroy(None) == cc.CC_OK
     assert lib.cc_plan_set_schedule(None, cc.CC_SCHEDULE_ORDERED, 0) == cc.CC_ERR_NULL
     assert lib.cc_plan_schedule(None, None, None) == cc.CC_ERR_NULL
+    assert lib.cc_plan_autotune(None, C.byref(hp), 0, 0x1000, None, None, None) == cc.CC_ERR_NULL
     assert "plan is NULL" in cc.cc_last_error()
 
 

@@ -169,3 +169,44 @@ def test_schedule_selection_and_errors():
     cc.cc_plan_set_schedule(sh.plans[0], ORDERED, 64)
     assert cc.cc_plan_schedule(sh.plans[0]) == (ORDERED, 2)                       # never more than pairs of chunks
     sh.destroy()
+
+
+@pytest.mark.parametrize("optimizer", [0, 1])
+def test_autotune_keeps_a_valid_schedule_and_the_results(optimizer):
+    numels = [4096 * 300 + 17, 4096 * 200, 5]
+    fn = cc.cc_fused_adam_step if optimizer == 0 else cc.cc_fused_lamb_step
+    tuned = Shard(numels, wds_for(numels), 4, chunk_elems=4096, align_elems=8)
+    plain = Shard(numels, wds_for(numels), 4, chunk_elems=4096, align_elems=8, schedule=cc.CC_SCHEDULE_PER_CHUNK)
+    for sh in (tuned, plain):
+        seeded_state(sh, 17)
+        seeded_grads(sh, 1700, 1e-2)
+    ghp, _ = hyper_pair(step=2)
+    committed = [x.clone() for x in (tuned.w[0], tuned.m[0], tuned.v[0], tuned.w16[0])]
+    best_ms, per_chunk_ms = cc.cc_plan_autotune(tuned.plans[0], ghp, tuned.flag, optimizer)
+    assert 0.0 < best_ms <= per_chunk_ms * 1.0001
+    sched, wgs = cc.cc_plan_schedule(tuned.plans[0])
+    assert sched in (cc.CC_SCHEDULE_PER_CHUNK, cc.CC_SCHEDULE_ORDERED) and wgs >= 1
+    for a, b in zip(committed, (tuned.w[0], tuned.m[0], tuned.v[0], tuned.w16[0])):
+        assert torch.equal(a, b)                                   # the trial steps left the committed copy alone
+    assert tuned.step(fn, ghp) == 0 and plain.step(fn, ghp) == 0
+    for k in range(len(numels)):
+        assert torch.equal(tuned.w_of(k), plain.w_of(k)) and torch.equal(tuned.m_of(k), plain.m_of(k))
+        assert torch.equal(tuned.v_of(k), plain.v_of(k)) and torch.equal(tuned.w16_of(k).view(torch.int16), plain.w16_of(k).view(torch.int16))
+    tuned.destroy(); plain.destroy()
+
+
+def test_autotune_rejects_in_place_plans_and_bad_arguments():
+    sh = Shard([4096 * 4], [0.0], 2, chunk_elems=4096, align_elems=8, in_place=True)
+    with pytest.raises(cc.CcError) as e:
+        cc.cc_plan_autotune(sh.plans[0], cc.Hyper(skip_mode=1), sh.flag, 0)
+    assert e.value.code == cc.CC_ERR_ALIAS
+    sh.destroy()
+    sh = Shard([4096 * 4], [0.0], 2, chunk_elems=4096, align_elems=8)
+    before = cc.cc_plan_schedule(sh.plans[0])
+    with pytest.raises(cc.CcError) as e:
+        cc.cc_plan_autotune(sh.plans[0], cc.Hyper(), sh.flag, 2)
+    assert e.value.code == cc.CC_ERR_ARG
+    with pytest.raises(cc.CcError):
+        cc.cc_plan_autotune(sh.plans[0], cc.Hyper(step=0), sh.flag, 0)
+    assert cc.cc_plan_schedule(sh.plans[0]) == before
+    sh.destroy()
