@@ -103,6 +103,12 @@ int64_t cc_chunk_count(const uint64_t *numels, int32_t T, int32_t chunk_elems);
 int64_t cc_chunk_table_fill(const uint64_t *numels, int32_t T, int32_t chunk_elems,
                             uint32_t *table, int64_t capacity);
 
+/* The same entries in the order the ordered schedule (cc_plan_set_schedule) works through them: every full chunk
+ * first, in tensor order, then the tensors' short last chunks.  *full_chunks (may be NULL) receives the number of
+ * full chunks.  Returns the number of entries written, or < 0 on error / too small. */
+int64_t cc_ordered_table_fill(const uint64_t *numels, int32_t T, int32_t chunk_elems,
+                              uint32_t *table, int64_t capacity, int64_t *full_chunks);
+
 /* Default chunk size in elements for large shards (a tuning choice of this library; the paper's buckets hold
  * 2^10).  Shards below 64 Mi elements default to 1024-element chunks (faster there in the size sweep). */
 int32_t cc_default_chunk_elems(void);

@@ -51,6 +51,8 @@ class cc_epilogue(C.Structure):
 EXPORTS = {
     "cc_chunk_count": (C.c_int64, [C.POINTER(C.c_uint64), C.c_int32, C.c_int32]),
     "cc_chunk_table_fill": (C.c_int64, [C.POINTER(C.c_uint64), C.c_int32, C.c_int32, C.POINTER(C.c_uint32), C.c_int64]),
+    "cc_ordered_table_fill": (C.c_int64, [C.POINTER(C.c_uint64), C.c_int32, C.c_int32, C.POINTER(C.c_uint32), C.c_int64,
+                                          C.POINTER(C.c_int64)]),
     "cc_default_chunk_elems": (C.c_int32, []),
     "cc_plan_create": (C.c_int, [C.POINTER(cc_tensor), C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_void_p)]),
     "cc_plan_create_ex": (C.c_int, [C.POINTER(cc_tensor), C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_void_p)]),
@@ -190,6 +192,16 @@ def cc_chunk_table_fill(numels: Sequence[int], chunk_elems: int = 0, capacity: O
     table = (C.c_uint32 * max(2 * n, 2))()
     k = _check(load().cc_chunk_table_fill(arr, len(numels), chunk_elems, table, n))
     return [(table[2 * i], table[2 * i + 1]) for i in range(k)]
+
+
+def cc_ordered_table_fill(numels: Sequence[int], chunk_elems: int = 0):
+    """([(tensor, chunk)] in the ordered schedule's order, number of full chunks)."""
+    n = cc_chunk_count(numels, chunk_elems)
+    arr = (C.c_uint64 * max(len(numels), 1))(*numels)
+    table = (C.c_uint32 * max(2 * n, 2))()
+    nfull = C.c_int64()
+    k = _check(load().cc_ordered_table_fill(arr, len(numels), chunk_elems, table, n, C.byref(nfull)))
+    return [(table[2 * i], table[2 * i + 1]) for i in range(k)], nfull.value
 
 
 # ---- plan ----

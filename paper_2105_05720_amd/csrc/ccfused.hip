@@ -150,6 +150,29 @@ int64_t cc_chunk_table_fill(const uint64_t *numels, int32_t T, int32_t chunk_ele
     return k;
 }
 
+int64_t cc_ordered_table_fill(const uint64_t *numels, int32_t T, int32_t chunk_elems, uint32_t *table, int64_t capacity,
+                              int64_t *full_chunks)
+{
+    const int64_t need = cc_chunk_count(numels, T, chunk_elems);
+    if (need < 0) return need;
+    if (!table && need > 0) return fail(CC_ERR_NULL, "cc_ordered_table_fill: table is NULL");
+    if (capacity < need) return fail(CC_ERR_ARG, "table capacity %lld < %lld chunks", (long long)capacity, (long long)need);
+    const uint64_t ce = (uint64_t)resolve_chunk(chunk_elems);
+    int64_t k = 0, nfull = 0;
+    for (int pass = 0; pass < 2; ++pass) {             // full chunks in tensor order, then the short last chunks
+        for (int32_t t = 0; t < T; ++t) {
+            const uint64_t full = numels[t] / ce, all = (numels[t] + ce - 1) / ce;
+            for (uint64_t i = pass == 0 ? 0 : full; i < (pass == 0 ? full : all); ++i, ++k) {
+                table[2 * k] = (uint32_t)t;
+                table[2 * k + 1] = (uint32_t)i;
+            }
+        }
+        if (pass == 0) nfull = k;
+    }
+    if (full_chunks) *full_chunks = nfull;
+    return k;
+}
+
 int cc_plan_create(const cc_tensor *tensors, int32_t T, int32_t R, int32_t chunk_elems, cc_plan **out)
 {
     return cc_plan_create_ex(tensors, T, R, chunk_elems, CC_GRAD_F16, out);
@@ -244,15 +267,9 @@ int cc_plan_create_ex(const cc_tensor *tensors, int32_t T, int32_t R, int32_t ch
         return fail(CC_ERR_NOMEM, "cc_plan_create: out of host memory");
     }
     {
-        size_t k = 0;
-        for (int pass = 0; pass < 2; ++pass) {
-            for (int64_t i = 0; i < chunks; ++i) {
-                const uint32_t t = table[2 * (size_t)i], idx = table[2 * (size_t)i + 1];
-                const bool full = ((uint64_t)idx + 1) * (uint64_t)ce <= numels[t];
-                if (full == (pass == 0)) { ordered_table[2 * k] = t; ordered_table[2 * k + 1] = idx; ++k; }
-            }
-            if (pass == 0) p->nfull = (uint32_t)k;
-        }
+        int64_t nfull = 0;
+        cc_ordered_table_fill(numels.data(), T, ce, ordered_table.data(), chunks, &nfull);
+        p->nfull = (uint32_t)nfull;
     }
 
 #define PLAN_TRY(expr)                                                                             \

@@ -59,6 +59,24 @@ def test_chunk_table_against_brute_force(ce):
     assert all(covered[t] == n for t, n in enumerate(numels))
 
 
+@pytest.mark.parametrize("ce", [1024, 4096])
+def test_ordered_table_against_brute_force(ce):
+    """The ordered schedule's table: the same entries as the plain table, every full chunk first (tensor order),
+    then the short last chunks; nfull counts the former."""
+    rng = np.random.default_rng(ce + 1)
+    numels = [0, 1, ce - 1, ce, ce + 1, 5 * ce, 0, 3, 7 * ce] + [int(x) for x in rng.integers(0, 20 * ce, 20)]
+    plain = brute_table(numels, ce)
+    full = [(t, i) for t, i in plain if (i + 1) * ce <= numels[t]]
+    short = [(t, i) for t, i in plain if (i + 1) * ce > numels[t]]
+    table, nfull = cc.cc_ordered_table_fill(numels, ce)
+    assert nfull == len(full) == sum(n // ce for n in numels)
+    assert table == full + short
+    assert sorted(table) == sorted(plain) and len(short) == sum(1 for n in numels if n % ce)
+    assert cc.cc_ordered_table_fill([], ce) == ([], 0)
+    assert cc.cc_ordered_table_fill([ce * 3], ce) == ([(0, 0), (0, 1), (0, 2)], 3)
+    assert cc.cc_ordered_table_fill([5], ce) == ([(0, 0)], 0)
+
+
 def test_chunk_table_default_and_errors():
     assert cc.cc_default_chunk_elems() % 1024 == 0
     assert cc.cc_chunk_count([10000], 0) == -(-10000 // cc.cc_default_chunk_elems())
