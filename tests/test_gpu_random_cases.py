@@ -1,5 +1,5 @@
-"""Seeded random sweep over list shapes, R, modes, hyper-parameters, gradient type, chunk size and pipeline:
-every case is compared with the oracle element by element (same bar as the hand-picked cases)."""
+"""Seeded random sweep over list shapes, R, modes, hyper-parameters, gradient type, chunk size, schedule and
+pipeline: every case is compared with the oracle element by element (same bar as the hand-picked cases)."""
 import numpy as np
 import pytest
 import torch
@@ -48,12 +48,9 @@ def draw_case(rng):
     return case
 
 
-@pytest.mark.parametrize("seed", range(40))
-def test_random_case(seed):
-    rng = np.random.default_rng(1000 + seed)
-    c = draw_case(rng)
+def run_case(seed, c, rng, **shard_kw):
     shard = Shard(c["numels"], c["wds"], c["R"], chunk_elems=c["chunk"], in_place=c["in_place"], align_elems=8,
-                  grad_dtype=torch.float32 if c["f32"] else torch.float16)
+                  grad_dtype=torch.float32 if c["f32"] else torch.float16, **shard_kw)
     seeded_state(shard, seed)
     ost = OracleState(shard, range(len(c["numels"])))
     if c["lamb"]:
@@ -65,3 +62,20 @@ def test_random_case(seed):
     run_steps(shard, ost, gpu_fn, ofn, hps, "random case %d %r" % (seed, c),
               lambda i: seeded_grads(shard, seed * 10 + i, c["gstd"] * c["hp"]["loss_scale"] if c["hp"]["loss_scale"] <= 128 else c["gstd"]))
     shard.destroy()
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_case(seed):
+    rng = np.random.default_rng(1000 + seed)
+    run_case(seed, draw_case(rng), rng)
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_case_ordered_schedule(seed):
+    """The same kind of draw on 4096-element chunks under the ordered persistent schedule, with a random number of
+    workgroups (1 .. more than there are chunks) and larger tensors, so that several blocks of the table are in play."""
+    rng = np.random.default_rng(5000 + seed)
+    c = draw_case(rng)
+    c["chunk"] = 4096
+    c["numels"] = [n * int(rng.choice([1, 1, 3, 8])) for n in c["numels"]]
+    run_case(seed, c, rng, schedule=cc.CC_SCHEDULE_ORDERED, workgroups=int(rng.choice([1, 2, 3, 5, 8, 13, 32, 100, 0])))
