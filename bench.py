@@ -25,7 +25,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 
 # HBM bytes per launch of the headline kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by what
 # the same counter reads for the plain copy kernel: default chunk size and schedule, fp16 slices, scattered list only.
-MEASURED_TRAFFIC_BYTES = {2: 9.4490e9 + 4.7098e9, 3: 1.3499e10 + 4.7131e9}     # profiles/fused_adam_config2.md, fused_lamb_config3.md
+MEASURED_TRAFFIC_BYTES = {2: 9.4495e9 + 4.7096e9, 3: 1.3500e10 + 4.7133e9,        # profiles/fused_adam_config2.md, fused_lamb_config3.md
+                          4: 4.3673e10 + 2.1818e10, 5: 4.1659e10 + 1.4574e10}     # profiles/fused_adam_config4.md, fused_lamb_config5.md
 
 
 GRAD_BYTES = 2                 # bytes per gradient element (set to 4 by --grad-dtype f32)
