@@ -680,6 +680,7 @@ __device__ __forceinline__ void block_sum2(double &a, double &b)
     if (kWaves > 1) {
         __shared__ double lds[2][kWaves];
         const int wave = threadIdx.x >> 6;
+        __syncthreads();                 // a persistent workgroup calls this once per chunk: the last call's reads are over
         if ((threadIdx.x & 63) == 0) { lds[0][wave] = a; lds[1][wave] = b; }
         __syncthreads();
         a = lds[0][0];
