@@ -31,6 +31,9 @@
 #ifdef __cplusplus
 extern "C" {
 #endif
+#if defined(__GNUC__)
+#pragma GCC visibility push(default)   /* the library itself is built with hidden visibility: only these are exported */
+#endif
 
 #define CC_MAX_R 16            /* most gradient slices one element can be reduced from */
 #define CC_VERSION 100
@@ -258,6 +261,9 @@ int cc_device_info(int32_t *compute_units, int32_t *memory_clock_khz, int32_t *m
 const char *cc_last_error(void);
 int cc_version(void);
 
+#if defined(__GNUC__)
+#pragma GCC visibility pop
+#endif
 #ifdef __cplusplus
 }
 #endif

@@ -1,23 +1,30 @@
-"""Builds libccfused.so for gfx950 with hipcc, in-tree (next to this file)."""
+"""Builds libccfused.so for gfx950 with hipcc, in-tree (next to this file).
+
+The library is several translation units (one per kernel family) only so that they compile side by side; each is
+compiled to an object file and the objects are linked into one shared library."""
 from __future__ import annotations
 
 import os
 import subprocess
 import sys
+from concurrent.futures import ThreadPoolExecutor
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(_HERE)
-SRC = os.path.join(_HERE, "csrc", "ccfused.hip")
-DEPS = [SRC, os.path.join(_HERE, "csrc", "kernels.hip.h"), os.path.join(ROOT, "include", "ccfused.h")]
+CSRC = os.path.join(_HERE, "csrc")
+SOURCES = [os.path.join(CSRC, n) for n in ("ccfused.hip", "launch_adam_f16.hip", "launch_adam_f32.hip", "launch_lamb.hip",
+                                           "launch_unfused.hip")]
+DEPS = SOURCES + [os.path.join(CSRC, "kernels.hip.h"), os.path.join(CSRC, "plan.hpp"), os.path.join(ROOT, "include", "ccfused.h")]
 LIB = os.path.join(_HERE, "libccfused.so")
+OBJ_DIR = os.path.join(_HERE, "_build")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
-    "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
+    "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fvisibility=hidden",
     "-ffp-contract=off",                                              # fused multiply-adds are written out by hand
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",      # no packed-fp32 instructions
     "-Wall", "-Wextra", "-Wno-unused-parameter",
-    "-I", os.path.join(ROOT, "include"), "-I", os.path.join(_HERE, "csrc"),
+    "-I", os.path.join(ROOT, "include"), "-I", CSRC,
 ]
 
 
@@ -32,10 +39,23 @@ def build_library(force: bool = True, extra=()) -> str:
     """Compile the HIP library.  force=False skips the compile when the built file is newer than its sources."""
     if not force and not is_stale():
         return LIB
-    tmp = LIB + ".tmp%d" % os.getpid()
-    cmd = [HIPCC] + FLAGS + list(extra) + ["-o", tmp, SRC]
-    subprocess.check_call(cmd)
-    os.replace(tmp, LIB)
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    tag = ".%d" % os.getpid()
+    objs = [os.path.join(OBJ_DIR, os.path.basename(src)[:-4] + tag + ".o") for src in SOURCES]
+
+    def compile_one(pair):
+        src, obj = pair
+        subprocess.check_call([HIPCC] + FLAGS + list(extra) + ["-c", "-o", obj, src])
+    try:
+        with ThreadPoolExecutor(max_workers=min(len(SOURCES), os.cpu_count() or 1)) as pool:
+            list(pool.map(compile_one, zip(SOURCES, objs)))
+        tmp = LIB + ".tmp%d" % os.getpid()
+        subprocess.check_call([HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", tmp] + objs)
+        os.replace(tmp, LIB)
+    finally:
+        for obj in objs:
+            if os.path.exists(obj):
+                os.remove(obj)
     return LIB
 
 

@@ -9,22 +9,17 @@
 #include <new>
 #include <vector>
 
-#include "ccfused.h"
-#include "kernels.hip.h"
+#include "plan.hpp"
 
 using namespace ccf;
 
 namespace {
 
-constexpr int32_t kDefaultChunkElems = 4096;     // one sweep of a 512-thread workgroup (2 groups x 512 lanes x 4 elements)
-constexpr int32_t kSmallChunkElems = 1024;       // one sweep of a 128-thread workgroup: more workgroups for small shards
-constexpr uint64_t kSmallShardElems = 64u << 20; // below this many elements the default chunk is the small one (size sweep)
-constexpr int32_t kMaxChunkElems = 1 << 24;      // lane offsets inside a chunk are 32-bit byte offsets
-constexpr int kBigBlock = 512, kSmallBlock = 128;
-constexpr int kOrderedMaxF32Slices = 4;           // fp32 slices: measured faster up to 4, slower at 8 (two chunks of 8 take 209 VGPRs)
-constexpr int64_t kOrderedMinChunksPerCu = 8;    // below this many chunks per compute unit a plan keeps one workgroup per chunk
-
 thread_local char g_err[512] = "";
+
+}  // namespace
+
+namespace ccf {
 
 int fail(cc_status code, const char *fmt, ...)
 {
@@ -35,11 +30,16 @@ int fail(cc_status code, const char *fmt, ...)
     return (int)code;
 }
 
-#define HIP_TRY(expr)                                                                              \
-    do {                                                                                           \
-        hipError_t e_ = (expr);                                                                    \
-        if (e_ != hipSuccess) return fail(CC_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_));     \
-    } while (0)
+int launched(const char *what)
+{
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(CC_ERR_HIP, "launch of %s failed: %s", what, hipGetErrorString(e));
+    return CC_OK;
+}
+
+}  // namespace ccf
+
+namespace {
 
 int32_t resolve_chunk(int32_t chunk_elems, uint64_t total_elems = ~0ull)
 {
@@ -61,43 +61,7 @@ int overlap(const void *a, const void *b, uint64_t bytes)
 
 }  // namespace
 
-struct cc_plan {
-    int32_t T = 0, R = 0, chunk_elems = 0;
-    int block = kBigBlock;                  // threads per workgroup of the streaming kernels
-    FlagScratch *d_flag_scratch = nullptr;  // {done, bad}, zero between launches
-    bool ordered = false;                   // large shards: persistent workgroups take chunks in table order
-    int32_t schedule = CC_SCHEDULE_AUTO;    // what the caller asked for
-    unsigned ordered_grid = 0;              // workgroups of the ordered schedule (one per compute unit unless set)
-    int32_t cus = 0;                        // compute units of the device the plan was created on
-    int32_t single = -1;                    // index of the only tensor with elements, or -1 if there are several (or none)
-    uint32_t nfull = 0;                     // full chunks; the ordered table lists them first, short last chunks behind
-    Chunk *d_chunks_ordered = nullptr;
-    WorkQueue *d_queue = nullptr;           // zero between launches
-    int64_t chunks = 0;
-    uint64_t numel = 0;
-    bool in_place = false;                  // some tensor has out == in
-    bool grad_f32 = false;                  // gradient slices are fp32 instead of fp16
-    std::vector<DevTensor> host_tensors;    // host mirror of the device descriptors
-    std::vector<uint64_t> gsum_offset;      // element offset of each tensor in the unfused fp32 buffer
-    uint64_t gsum_elems = 0;
-    DevTensor *d_tensors = nullptr;
-    Chunk *d_chunks = nullptr;
-    double *d_partials = nullptr;           // 2 per chunk (LAMB)
-    double *d_sums = nullptr;               // 2 per tensor (LAMB)
-    float *d_gsum = nullptr;                // unfused pipelines, allocated on first use
-};
-
 namespace {
-
-// Workgroups of an ordered launch: one per compute unit unless the caller chose a number; never more than there
-// are pairs of chunks (every workgroup owns two entries without asking).
-unsigned ordered_grid(const cc_plan *p)
-{
-    unsigned g = p->ordered_grid ? p->ordered_grid : (unsigned)p->cus;
-    const unsigned most = (unsigned)((p->chunks + 1) / 2);
-    if (g > most) g = most;
-    return g ? g : 1u;
-}
 
 void resolve_schedule(cc_plan *p)
 {
@@ -406,13 +370,6 @@ int check_step(const cc_plan *p, const cc_hparams *hp, const void *flag, Opt opt
     return CC_OK;
 }
 
-int launched(const char *what)
-{
-    const hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return fail(CC_ERR_HIP, "launch of %s failed: %s", what, hipGetErrorString(e));
-    return CC_OK;
-}
-
 // Allocates the fp32 reduced-gradient buffer of the unfused pipelines and points every descriptor at it.
 int ensure_gsum(cc_plan *p)
 {
@@ -421,210 +378,6 @@ int ensure_gsum(cc_plan *p)
     for (int32_t t = 0; t < p->T; ++t) p->host_tensors[(size_t)t].gsum = p->d_gsum + p->gsum_offset[(size_t)t];
     HIP_TRY(hipMemcpy(p->d_tensors, p->host_tensors.data(), sizeof(DevTensor) * (size_t)p->T, hipMemcpyHostToDevice));
     return CC_OK;
-}
-
-#define FOR_EACH_R(X) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13) X(14) X(15) X(16)
-
-// Every streaming kernel exists for two workgroup sizes; the plan picks one from its chunk size.
-#define BY_BLOCK(p, CALL)                      \
-    do {                                       \
-        if ((p)->block == kBigBlock) { constexpr int BLK = kBigBlock; CALL; } \
-        else { constexpr int BLK = kSmallBlock; CALL; }                       \
-    } while (0)
-
-// Chunks per ticket of the ordered schedule, by how many bytes a kernel moves per element: one counter serves the
-// whole device at about one ticket per 12 ns, so a ticket has to stand for well over 100 KB of traffic.
-enum SpanKind { kSpanAdam, kSpanPhase1, kSpanPhase2, kSpanReduce, kSpanFromSum, kSpanCast, kSpanKinds };
-uint32_t span_of(SpanKind k)
-{
-    static const uint32_t chunks_per_ticket[kSpanKinds] = {1, 1, 2, 2, 1, 4};      // measured on the BERT-Large list
-    return chunks_per_ticket[k];
-}
-
-// Arguments every ordered kernel starts with.
-#define ORDERED_ARGS(p, kind) (p)->d_tensors, (p)->d_chunks_ordered, (p)->nfull, (uint32_t)(p)->chunks, span_of(kind)
-
-template <int MODE, int BLK, bool GF32>
-void launch_fused_adam_r(const cc_plan *p, const StepScalars &s, int32_t *flag, hipStream_t st)
-{
-    if (p->ordered) {
-        const dim3 grid(ordered_grid(p)), block(kBigBlock);
-        switch (p->R) {
-#define CASE(r) case r: hipLaunchKernelGGL((fused_adam_ordered_kernel<r, MODE, kBigBlock, GF32>), grid, block, 0, st, ORDERED_ARGS(p, kSpanAdam), s, p->d_queue, flag); break;
-            FOR_EACH_R(CASE)
-#undef CASE
-        }
-        return;
-    }
-    const dim3 grid((unsigned)p->chunks), block(BLK);
-    if (p->single >= 0) {                  // one tensor: no table, descriptor in the kernel arguments
-        const DevTensor &t = p->host_tensors[(size_t)p->single];
-        switch (p->R) {
-#define CASE(r) case r: hipLaunchKernelGGL((fused_adam_flat_kernel<r, MODE, BLK, GF32>), grid, block, 0, st, t, s, p->d_flag_scratch, flag); break;
-            FOR_EACH_R(CASE)
-#undef CASE
-        }
-        return;
-    }
-    switch (p->R) {
-#define CASE(r) case r: hipLaunchKernelGGL((fused_adam_kernel<r, MODE, BLK, GF32>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, p->d_flag_scratch, flag); break;
-        FOR_EACH_R(CASE)
-#undef CASE
-    }
-}
-
-template <int MODE, int BLK>
-void launch_fused_adam(const cc_plan *p, const StepScalars &s, int32_t *flag, hipStream_t st)
-{
-    if (p->grad_f32) launch_fused_adam_r<MODE, BLK, true>(p, s, flag, st);
-    else launch_fused_adam_r<MODE, BLK, false>(p, s, flag, st);
-}
-
-template <int BLK, bool GF32>
-void launch_lamb_phase1_r(const cc_plan *p, const StepScalars &s, int32_t *flag, hipStream_t st)
-{
-    if (p->ordered) {
-        const dim3 grid(ordered_grid(p)), block(kBigBlock);
-        switch (p->R) {
-#define CASE(r) case r: hipLaunchKernelGGL((lamb_phase1_ordered_kernel<r, kBigBlock, GF32>), grid, block, 0, st, ORDERED_ARGS(p, kSpanPhase1), s, p->d_partials, p->d_queue, flag); break;
-            FOR_EACH_R(CASE)
-#undef CASE
-        }
-        return;
-    }
-    const dim3 grid((unsigned)p->chunks), block(BLK);
-    switch (p->R) {
-#define CASE(r) case r: hipLaunchKernelGGL((lamb_phase1_kernel<r, BLK, GF32>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, p->d_partials, p->d_flag_scratch, flag); break;
-        FOR_EACH_R(CASE)
-#undef CASE
-    }
-}
-
-template <int BLK>
-void launch_lamb_phase1(const cc_plan *p, const StepScalars &s, int32_t *flag, hipStream_t st)
-{
-    if (p->grad_f32) launch_lamb_phase1_r<BLK, true>(p, s, flag, st);
-    else launch_lamb_phase1_r<BLK, false>(p, s, flag, st);
-}
-
-template <int BLK, bool GF32>
-void launch_reduce_r(const cc_plan *p, const StepScalars &s, int32_t *flag, hipStream_t st)
-{
-    if (p->ordered) {
-        const dim3 grid(ordered_grid(p)), block(kBigBlock);
-        switch (p->R) {
-#define CASE(r) case r: hipLaunchKernelGGL((reduce_ordered_kernel<r, kBigBlock, GF32>), grid, block, 0, st, ORDERED_ARGS(p, kSpanReduce), s, p->d_queue, flag); break;
-            FOR_EACH_R(CASE)
-#undef CASE
-        }
-        return;
-    }
-    const dim3 grid((unsigned)p->chunks), block(BLK);
-    switch (p->R) {
-#define CASE(r) case r: hipLaunchKernelGGL((reduce_kernel<r, BLK, GF32>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, p->d_flag_scratch, flag); break;
-        FOR_EACH_R(CASE)
-#undef CASE
-    }
-}
-
-template <int BLK>
-void launch_reduce(const cc_plan *p, const StepScalars &s, int32_t *flag, hipStream_t st)
-{
-    if (p->grad_f32) launch_reduce_r<BLK, true>(p, s, flag, st);
-    else launch_reduce_r<BLK, false>(p, s, flag, st);
-}
-
-template <int BLK, bool SUM16>
-void launch_adam_from_sum(const cc_plan *p, const StepScalars &s, const int32_t *flag, hipStream_t st, int mode)
-{
-    if (p->ordered) {
-        const dim3 grid(ordered_grid(p)), block(kBigBlock);
-        switch (mode) {
-            case 0: hipLaunchKernelGGL((adam_from_sum_ordered_kernel<0, kBigBlock, SUM16>), grid, block, 0, st, ORDERED_ARGS(p, kSpanFromSum), s, p->d_queue, flag); break;
-            case 1: hipLaunchKernelGGL((adam_from_sum_ordered_kernel<1, kBigBlock, SUM16>), grid, block, 0, st, ORDERED_ARGS(p, kSpanFromSum), s, p->d_queue, flag); break;
-            case 2: hipLaunchKernelGGL((adam_from_sum_ordered_kernel<2, kBigBlock, SUM16>), grid, block, 0, st, ORDERED_ARGS(p, kSpanFromSum), s, p->d_queue, flag); break;
-            default: hipLaunchKernelGGL((adam_from_sum_ordered_kernel<3, kBigBlock, SUM16>), grid, block, 0, st, ORDERED_ARGS(p, kSpanFromSum), s, p->d_queue, flag); break;
-        }
-        return;
-    }
-    const dim3 grid((unsigned)p->chunks), block(BLK);
-    switch (mode) {
-        case 0: hipLaunchKernelGGL((adam_from_sum_kernel<0, BLK, SUM16>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag); break;
-        case 1: hipLaunchKernelGGL((adam_from_sum_kernel<1, BLK, SUM16>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag); break;
-        case 2: hipLaunchKernelGGL((adam_from_sum_kernel<2, BLK, SUM16>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag); break;
-        default: hipLaunchKernelGGL((adam_from_sum_kernel<3, BLK, SUM16>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag); break;
-    }
-}
-
-template <int BLK>
-void launch_reduce_half(const cc_plan *p, const StepScalars &s, int32_t *flag, hipStream_t st)
-{
-    if (p->ordered) {
-        const dim3 grid(ordered_grid(p)), block(kBigBlock);
-        switch (p->R) {
-#define CASE(r) case r: hipLaunchKernelGGL((reduce_half_ordered_kernel<r, kBigBlock>), grid, block, 0, st, ORDERED_ARGS(p, kSpanReduce), s, p->d_queue, flag); break;
-            FOR_EACH_R(CASE)
-#undef CASE
-        }
-        return;
-    }
-    const dim3 grid((unsigned)p->chunks), block(BLK);
-    switch (p->R) {
-#define CASE(r) case r: hipLaunchKernelGGL((reduce_half_kernel<r, BLK>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, p->d_flag_scratch, flag); break;
-        FOR_EACH_R(CASE)
-#undef CASE
-    }
-}
-
-template <int BLK>
-void launch_fused_adam_mode(const cc_plan *p, const StepScalars &s, int32_t *flag, hipStream_t st, int mode)
-{
-    switch (mode) {
-        case 0: launch_fused_adam<0, BLK>(p, s, flag, st); break;
-        case 1: launch_fused_adam<1, BLK>(p, s, flag, st); break;
-        case 2: launch_fused_adam<2, BLK>(p, s, flag, st); break;
-        default: launch_fused_adam<3, BLK>(p, s, flag, st); break;
-    }
-}
-
-// A plan without chunks launches no streaming kernel, so the flag is cleared by a one-thread kernel (a kernel
-// rather than a memset node, so that the call can still be captured into a HIP graph).
-int clear_flag(int32_t *flag, hipStream_t st)
-{
-    hipLaunchKernelGGL(clear_flag_kernel, dim3(1), dim3(1), 0, st, flag);
-    return launched("clear_flag_kernel");
-}
-
-int lamb_phase2_impl(cc_plan *p, const StepScalars &s, const int32_t *flag, hipStream_t st, bool emit16)
-{
-    if (p->chunks == 0) return CC_OK;
-    if (p->ordered) {
-        const dim3 grid(ordered_grid(p)), block(kBigBlock);
-        if (emit16) hipLaunchKernelGGL((lamb_phase2_ordered_kernel<true, kBigBlock>), grid, block, 0, st, ORDERED_ARGS(p, kSpanPhase2), s, p->d_sums, p->d_queue, flag);
-        else hipLaunchKernelGGL((lamb_phase2_ordered_kernel<false, kBigBlock>), grid, block, 0, st, ORDERED_ARGS(p, kSpanPhase2), s, p->d_sums, p->d_queue, flag);
-        return launched("lamb_phase2_ordered_kernel");
-    }
-    const dim3 grid((unsigned)p->chunks);
-    if (emit16) BY_BLOCK(p, hipLaunchKernelGGL((lamb_phase2_kernel<true, BLK>), grid, dim3(BLK), 0, st, p->d_tensors, p->d_chunks, s, p->d_sums, flag));
-    else BY_BLOCK(p, hipLaunchKernelGGL((lamb_phase2_kernel<false, BLK>), grid, dim3(BLK), 0, st, p->d_tensors, p->d_chunks, s, p->d_sums, flag));
-    return launched("lamb_phase2_kernel");
-}
-
-int lamb_norms(cc_plan *p, hipStream_t st)
-{
-    hipLaunchKernelGGL(lamb_norms_kernel, dim3((unsigned)p->T), dim3(kNormBlock), 0, st, p->d_tensors, p->d_partials, p->d_sums);
-    return launched("lamb_norms_kernel");
-}
-
-int cast_launch(cc_plan *p, const StepScalars &s, const int32_t *flag, hipStream_t st, int guarded)
-{
-    if (p->ordered) {
-        hipLaunchKernelGGL((cast_ordered_kernel<kBigBlock>), dim3(ordered_grid(p)), dim3(kBigBlock), 0, st, ORDERED_ARGS(p, kSpanCast), s, p->d_queue, flag, guarded);
-        return launched("cast_ordered_kernel");
-    }
-    const dim3 grid((unsigned)p->chunks);
-    BY_BLOCK(p, hipLaunchKernelGGL((cast_kernel<BLK>), grid, dim3(BLK), 0, st, p->d_tensors, p->d_chunks, s, flag, guarded));
-    return launched("cast_kernel");
 }
 
 }  // namespace
@@ -639,7 +392,8 @@ int cc_fused_adam_step(cc_plan *p, const cc_hparams *hp, int32_t *flag, void *st
     hipStream_t st = (hipStream_t)stream;
     if (p->chunks == 0) return clear_flag(flag, st);
     const int mode = (hp->skip_mode == 1 ? kModeGuard : 0) | (hp->adam_mode == 0 ? kModeL2 : 0);
-    BY_BLOCK(p, launch_fused_adam_mode<BLK>(p, s, flag, st, mode));
+    if (p->grad_f32) launch_fused_adam_f32(p, s, flag, st, mode);
+    else launch_fused_adam_f16(p, s, flag, st, mode);
     return launched("fused_adam_kernel");
 }
 
@@ -652,7 +406,7 @@ int cc_fused_lamb_phase1(cc_plan *p, const cc_hparams *hp, int32_t *flag, void *
     if (p->chunks == 0) {
         if ((rc = clear_flag(flag, st))) return rc;
     } else {
-        BY_BLOCK(p, launch_lamb_phase1<BLK>(p, s, flag, st));
+        launch_lamb_phase1(p, s, flag, st);
         if ((rc = launched("lamb_phase1_kernel"))) return rc;
     }
     return lamb_norms(p, st);
@@ -689,12 +443,11 @@ int cc_unfused_adam_step_ex(cc_plan *p, const cc_hparams *hp, int32_t *flag, voi
     if ((rc = ensure_gsum(p))) return rc;
     hipStream_t st = (hipStream_t)stream;
     if (p->chunks == 0) return clear_flag(flag, st);
-    if (sum16) BY_BLOCK(p, launch_reduce_half<BLK>(p, s, flag, st));
-    else BY_BLOCK(p, launch_reduce<BLK>(p, s, flag, st));
+    if (sum16) launch_reduce_half(p, s, flag, st);
+    else launch_reduce(p, s, flag, st);
     if ((rc = launched("reduce_kernel"))) return rc;
     const int mode = (hp->skip_mode == 1 ? kModeGuard : 0) | (hp->adam_mode == 0 ? kModeL2 : 0);
-    if (sum16) BY_BLOCK(p, (launch_adam_from_sum<BLK, true>(p, s, flag, st, mode)));
-    else BY_BLOCK(p, (launch_adam_from_sum<BLK, false>(p, s, flag, st, mode)));
+    launch_adam_from_sum(p, s, flag, st, mode, sum16);
     if ((rc = launched("adam_from_sum_kernel"))) return rc;
     return cast_launch(p, s, flag, st, hp->skip_mode == 0 ? 1 : 0);
 }
@@ -710,11 +463,9 @@ int cc_unfused_lamb_step(cc_plan *p, const cc_hparams *hp, int32_t *flag, void *
         if ((rc = clear_flag(flag, st))) return rc;
         return lamb_norms(p, st);
     }
-    const dim3 grid((unsigned)p->chunks);
-    BY_BLOCK(p, launch_reduce<BLK>(p, s, flag, st));
+    launch_reduce(p, s, flag, st);
     if ((rc = launched("reduce_kernel"))) return rc;
-    if (p->ordered) hipLaunchKernelGGL((lamb_phase1_from_sum_ordered_kernel<kBigBlock>), dim3(ordered_grid(p)), dim3(kBigBlock), 0, st, ORDERED_ARGS(p, kSpanFromSum), s, p->d_partials, p->d_queue);
-    else BY_BLOCK(p, hipLaunchKernelGGL((lamb_phase1_from_sum_kernel<BLK>), grid, dim3(BLK), 0, st, p->d_tensors, p->d_chunks, s, p->d_partials));
+    launch_lamb_phase1_from_sum(p, s, st);
     if ((rc = launched("lamb_phase1_from_sum_kernel"))) return rc;
     if ((rc = lamb_norms(p, st))) return rc;
     if ((rc = lamb_phase2_impl(p, s, flag, st, false))) return rc;

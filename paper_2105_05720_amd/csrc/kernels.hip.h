@@ -22,6 +22,7 @@
 //     window that slides through each stream, instead of the wide, drifting set that a grid of independent
 //     workgroups produces.  Small shards keep one workgroup per chunk (more parallel start-up, no ticket latency).
 #pragma once
+// (Kernels that are not templates are `static`: this header is included by several translation units.)
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -228,7 +229,7 @@ __device__ __forceinline__ void publish_flag(bool bad, FlagScratch *fs, int32_t 
 }
 
 // Only for a plan without any chunk: nothing else would write the flag.
-__global__ void clear_flag_kernel(int32_t *flag) { *flag = 0; }
+[[maybe_unused]] static __global__ void clear_flag_kernel(int32_t *flag) { *flag = 0; }
 
 // ---- the streaming skeleton --------------------------------------------------------------------------------------
 // An Op describes one kernel's per-element work:
@@ -842,7 +843,7 @@ __global__ __launch_bounds__(BLOCK) void lamb_phase1_from_sum_kernel(const DevTe
 // LAMB second level: one workgroup per tensor adds that tensor's chunk partials in a fixed order (four
 // independent strided partial sums per thread, then the block sum), so the result does not change between runs.
 constexpr int kNormBlock = 1024;
-__global__ __launch_bounds__(kNormBlock) void lamb_norms_kernel(const DevTensor *__restrict__ tensors,
+[[maybe_unused]] static __global__ __launch_bounds__(kNormBlock) void lamb_norms_kernel(const DevTensor *__restrict__ tensors,
                                                                 const double *__restrict__ partials,
                                                                 double *__restrict__ sums)
 {
@@ -1364,7 +1365,7 @@ __global__ __launch_bounds__(BLOCK) void epilogue_pointwise_kernel(EpilogueArgs 
 
 // Plain streaming copy, 16 bytes per lane, four accesses in flight per lane.
 constexpr int kCopyBlock = 256;
-__global__ __launch_bounds__(kCopyBlock) void copy_kernel(u32x4 *__restrict__ dst, const u32x4 *__restrict__ src,
+[[maybe_unused]] static __global__ __launch_bounds__(kCopyBlock) void copy_kernel(u32x4 *__restrict__ dst, const u32x4 *__restrict__ src,
                                                           uint64_t n16)
 {
     const uint64_t base = (uint64_t)blockIdx.x * (kCopyBlock * 4) + threadIdx.x;

@@ -1,0 +1,110 @@
+// Shared by the host-side translation units of ccfused: the plan, the error helpers and the launch entry points of
+// each kernel family.  The library is built from several sources only so that they compile in parallel; nothing
+// here is part of the C ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <vector>
+
+#include "ccfused.h"
+#include "kernels.hip.h"
+
+namespace ccf {
+
+constexpr int32_t kDefaultChunkElems = 4096;     // one sweep of a 512-thread workgroup (2 groups x 512 lanes x 4 elements)
+constexpr int32_t kSmallChunkElems = 1024;       // one sweep of a 128-thread workgroup: more workgroups for small shards
+constexpr uint64_t kSmallShardElems = 64u << 20; // below this many elements the default chunk is the small one (size sweep)
+constexpr int32_t kMaxChunkElems = 1 << 24;      // lane offsets inside a chunk are 32-bit byte offsets
+constexpr int kBigBlock = 512, kSmallBlock = 128;
+constexpr int kOrderedMaxF32Slices = 4;           // fp32 slices: measured faster up to 4, slower at 8 (two chunks of 8 take 209 VGPRs)
+constexpr int64_t kOrderedMinChunksPerCu = 8;    // below this many chunks per compute unit a plan keeps one workgroup per chunk
+
+// Records the message for cc_last_error() on this thread and returns the code.
+int fail(cc_status code, const char *fmt, ...);
+// CC_OK, or CC_ERR_HIP with the runtime's message if the last launch failed.
+int launched(const char *what);
+
+}  // namespace ccf
+
+#define HIP_TRY(expr)                                                                                   \
+    do {                                                                                                \
+        hipError_t e_ = (expr);                                                                         \
+        if (e_ != hipSuccess) return ccf::fail(CC_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_));     \
+    } while (0)
+
+struct cc_plan {
+    int32_t T = 0, R = 0, chunk_elems = 0;
+    int block = ccf::kBigBlock;                  // threads per workgroup of the streaming kernels
+    ccf::FlagScratch *d_flag_scratch = nullptr;  // {done, bad}, zero between launches
+    bool ordered = false;                   // large shards: persistent workgroups take chunks in table order
+    int32_t schedule = CC_SCHEDULE_AUTO;    // what the caller asked for
+    unsigned ordered_grid = 0;              // workgroups of the ordered schedule (one per compute unit unless set)
+    int32_t cus = 0;                        // compute units of the device the plan was created on
+    int32_t single = -1;                    // index of the only tensor with elements, or -1 if there are several (or none)
+    uint32_t nfull = 0;                     // full chunks; the ordered table lists them first, short last chunks behind
+    ccf::Chunk *d_chunks_ordered = nullptr;
+    ccf::WorkQueue *d_queue = nullptr;           // zero between launches
+    int64_t chunks = 0;
+    uint64_t numel = 0;
+    bool in_place = false;                  // some tensor has out == in
+    bool grad_f32 = false;                  // gradient slices are fp32 instead of fp16
+    std::vector<ccf::DevTensor> host_tensors;    // host mirror of the device descriptors
+    std::vector<uint64_t> gsum_offset;      // element offset of each tensor in the unfused fp32 buffer
+    uint64_t gsum_elems = 0;
+    ccf::DevTensor *d_tensors = nullptr;
+    ccf::Chunk *d_chunks = nullptr;
+    double *d_partials = nullptr;           // 2 per chunk (LAMB)
+    double *d_sums = nullptr;               // 2 per tensor (LAMB)
+    float *d_gsum = nullptr;                // unfused pipelines, allocated on first use
+};
+
+namespace ccf {
+
+// Workgroups of an ordered launch: one per compute unit unless the caller chose a number; never more than there
+// are pairs of chunks (every workgroup owns two entries without asking).
+inline unsigned ordered_grid(const cc_plan *p)
+{
+    unsigned g = p->ordered_grid ? p->ordered_grid : (unsigned)p->cus;
+    const unsigned most = (unsigned)((p->chunks + 1) / 2);
+    if (g > most) g = most;
+    return g ? g : 1u;
+}
+
+#define FOR_EACH_R(X) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13) X(14) X(15) X(16)
+
+// Every streaming kernel exists for two workgroup sizes; the plan picks one from its chunk size.
+#define BY_BLOCK(p, CALL)                      \
+    do {                                       \
+        if ((p)->block == kBigBlock) { constexpr int BLK = kBigBlock; CALL; } \
+        else { constexpr int BLK = kSmallBlock; CALL; }                       \
+    } while (0)
+
+// Chunks per ticket of the ordered schedule, by how many bytes a kernel moves per element: one counter serves the
+// whole device at about one ticket per 12 ns, so a ticket has to stand for well over 100 KB of traffic.
+enum SpanKind { kSpanAdam, kSpanPhase1, kSpanPhase2, kSpanReduce, kSpanFromSum, kSpanCast, kSpanKinds };
+inline uint32_t span_of(SpanKind k)
+{
+    static const uint32_t chunks_per_ticket[kSpanKinds] = {1, 1, 2, 2, 1, 4};      // measured on the BERT-Large list
+    return chunks_per_ticket[k];
+}
+
+// Arguments every ordered kernel starts with.
+#define ORDERED_ARGS(p, kind) (p)->d_tensors, (p)->d_chunks_ordered, (p)->nfull, (uint32_t)(p)->chunks, ccf::span_of(kind)
+
+
+// Launch entry points, one family per source file.  `mode` = kModeGuard | kModeL2 bits.
+void launch_fused_adam_f16(const cc_plan *p, const StepScalars &s, int32_t *flag, hipStream_t st, int mode);
+void launch_fused_adam_f32(const cc_plan *p, const StepScalars &s, int32_t *flag, hipStream_t st, int mode);
+void launch_lamb_phase1(const cc_plan *p, const StepScalars &s, int32_t *flag, hipStream_t st);
+void launch_lamb_phase1_from_sum(const cc_plan *p, const StepScalars &s, hipStream_t st);
+int lamb_phase2_impl(cc_plan *p, const StepScalars &s, const int32_t *flag, hipStream_t st, bool emit16);
+int lamb_norms(cc_plan *p, hipStream_t st);
+void launch_reduce(const cc_plan *p, const StepScalars &s, int32_t *flag, hipStream_t st);
+void launch_reduce_half(const cc_plan *p, const StepScalars &s, int32_t *flag, hipStream_t st);
+void launch_adam_from_sum(const cc_plan *p, const StepScalars &s, const int32_t *flag, hipStream_t st, int mode, bool sum16);
+int cast_launch(cc_plan *p, const StepScalars &s, const int32_t *flag, hipStream_t st, int guarded);
+int clear_flag(int32_t *flag, hipStream_t st);
+
+}  // namespace ccf
