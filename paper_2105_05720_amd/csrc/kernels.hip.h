@@ -320,8 +320,8 @@ struct WorkQueue {
 
 // The increasing sequence of table entries one workgroup works through.  The ticket for the block after the next
 // one is requested when a block is entered and only looked at when that later block is entered, a block's worth of
-// work later, so no wave waits on the atomic; its value reaches the other waves through LDS (two slots used in
-// turn: one barrier per block).
+// work later; the one wave that issues the atomic waits for it there and then, the others never do.  Its value
+// reaches them through LDS (two slots used in turn: one barrier per block).
 struct Entries {
     WorkQueue *q;
     uint32_t *slots;          // LDS, 2 words
