@@ -465,3 +465,26 @@ def test_adam_single_tensor_overflow_skip():
     hps = [hyper_pair(step=1), hyper_pair(step=2), hyper_pair(step=2)]
     run_steps(shard, ost, cc.cc_fused_adam_step, oracle.adam_step, hps, "adam single tensor skip", fill, expect_flags=[0, 1, 0])
     shard.destroy()
+
+
+@pytest.mark.parametrize("eps", [1e-8, 1e-3])
+def test_adam_extreme_state_magnitudes(eps):
+    """Second moments from 0 and 1e-30 up to 1e30 and first moments from 1e-20 to 1e18 against the oracle: the kernel
+    forms the quotient from the hardware reciprocal and square root, which must hold the bound over the whole range.
+    (Beyond ~1e36 the bias-corrected second moment v/(1 - beta2^t) leaves the fp32 range at small t, which fp32
+    arithmetic cannot follow; the fp64 oracle can, so that corner is not compared.)  One second moment and one first
+    moment per tensor, so that the rms floor of the bound is the magnitude under test."""
+    vs = [0.0, 1e-30, 1e-10, 1.0, 1e20, 1e30]
+    ms = [1e-20, -1e-20, 1.0, -1.0, 1e18, -1e18]
+    cases = [(v, m) for v in vs for m in ms]
+    numels = [300 + 7 * i for i in range(len(cases))]
+    shard = Shard(numels, [0.01 if i % 2 else 0.0 for i in range(len(cases))], 2, align_elems=8)
+    seeded_state(shard, 9)
+    for k, (v, m) in enumerate(cases):
+        shard.v_of(k).fill_(v)
+        shard.m_of(k).fill_(m)
+    ost = OracleState(shard, range(len(cases)))
+    hps = [hyper_pair(step=t, eps=eps, beta2=0.98) for t in (1, 5)]
+    run_steps(shard, ost, cc.cc_fused_adam_step, oracle.adam_step, hps, "adam extreme state eps=%g" % eps,
+              lambda i: seeded_grads(shard, 90 + i, 1e-3))
+    shard.destroy()
