@@ -76,29 +76,33 @@ uint16_t oracle_float_to_half(float x) { return oracle_double_to_half((double)x)
 
 /* ---- the reduced gradient of one element ---- */
 
-uint16_t oracle_float_to_half(float x);
+/* How the R incoming slices are typed, and what type the reduction hands on. */
+enum {
+    SLICES_F16 = 0,           /* fp16 slices, the sum is handed on in full (mixed precision, the paper's main case)      */
+    SLICES_F32 = 1,           /* fp32 slices (Section 6.1.1 evaluates Float 32 elements as well as Float 16)              */
+    SLICES_F16_SUM_F16 = 2    /* fp16 slices reduced by an fp16 all-reduce, as a framework's unfused baseline runs it
+                                 (Section 6.1.1, the AR-Opt schedule): the optimizer sees the sum as an fp16 tensor       */
+};
 
-/* The R slices hold fp16 bit patterns (mixed precision, the paper's main case) or, with grad_f32 == 1, fp32 values
- * (Section 6.1.1 reports Float 32 as qualitatively similar).  grad_f32 == 2 is the unfused baseline as a framework
- * runs it (Section 6.1.1, the AR-Opt schedule over an fp16 all-reduce): fp16 slices whose sum comes back from the
- * reduction as an fp16 tensor, i.e. the fp32 sum rounded to fp16 before the optimizer sees it. */
-static double reduced_sum(const void *const *g, int grad_f32, int R, uint64_t i)
+/* The "+" all-reduce of Fig. 4a, restricted to element i. */
+static double reduced_sum(const void *const *slice, int kind, int R, uint64_t i)
 {
-    double S = 0.0;
-    for (int r = 0; r < R; ++r)                                        /* the "+" all-reduce of Fig. 4a */
-        S += grad_f32 == 1 ? (double)((const float *)g[r])[i] : oracle_half_to_double(((const uint16_t *)g[r])[i]);
-    if (grad_f32 == 2) S = oracle_half_to_double(oracle_float_to_half((float)S));
-    return S;
+    double total = 0.0;
+    for (int r = 0; r < R; ++r)
+        total += kind == SLICES_F32 ? (double)((const float *)slice[r])[i]
+                                    : oracle_half_to_double(((const uint16_t *)slice[r])[i]);
+    if (kind == SLICES_F16_SUM_F16) total = oracle_half_to_double(oracle_float_to_half((float)total));
+    return total;
 }
 
-/* The overflow decision is taken on the sum as an fp32 value, the precision the GPU path reduces in: fp16 slices
- * cannot overflow it, fp32 slices can. */
-static int sum_overflows(double S) { return !isfinite((float)S); }
-
-static double unscale_divisor(float loss_scale, int R, int grad_average)
-{
-    return (double)loss_scale * (grad_average ? (double)R : 1.0);
-}
+/* The fused reduction works in the largest element type among the tensors of the computation (Section 5.2, "Mixed
+ * Precision"), which is fp32 here: fp16 slices are promoted to it, Float 32 slices (Section 6.1.1) have it already,
+ * and an all-reduce hands back a tensor of the type it worked in.  The reduced gradient therefore exists as an fp32
+ * value and is non-finite exactly when that fp32 value is: an inf/NaN input, infinities of both signs meeting, or a
+ * finite sum beyond the fp32 range.  Up to 16 promoted fp16 values cannot leave that range, so for fp16 slices the
+ * rule is "some input has all exponent bits set" (which the brute-force pin checks); only fp32 slices can reach the
+ * third case. */
+static int sum_overflows(double total) { return !isfinite((float)total); }
 
 /* 1 if any reduced gradient of this tensor is inf or NaN, else 0. */
 int oracle_grad_overflow(uint64_t n, int R, const void *const *g, int grad_f32)
@@ -119,6 +123,55 @@ void oracle_keep_tensor(uint64_t n, const float *w, const float *m, const float 
     }
 }
 
+/* ---- the method, per element ----
+ * Everything a step needs besides the element's own four numbers, formed once per tensor from the fp32 scalars
+ * of the C interface (promoted exactly). */
+typedef struct {
+    double lr, beta1, beta2, eps, decay;
+    double grad_divisor;      /* loss_scale, times R when the slices are averaged instead of summed              */
+    double unbias1, unbias2;  /* 1 - beta1^t, 1 - beta2^t with t the 1-based step (the Pow terms of Fig. 4a)    */
+    int decay_in_gradient;    /* L2 regularisation: the decay term joins the gradient; otherwise it joins u      */
+} step_terms;
+
+static step_terms make_step_terms(float lr, float beta1, float beta2, float eps, float decay, float loss_scale,
+                                  int step, int R, int grad_average, int decay_in_gradient)
+{
+    step_terms k;
+    k.lr = lr; k.beta1 = beta1; k.beta2 = beta2; k.eps = eps; k.decay = decay;
+    k.grad_divisor = (double)loss_scale * (grad_average ? (double)R : 1.0);
+    k.unbias1 = 1.0 - pow(k.beta1, (double)step);
+    k.unbias2 = 1.0 - pow(k.beta2, (double)step);
+    k.decay_in_gradient = decay_in_gradient;
+    return k;
+}
+
+/* What one element's reduced gradient does to its moments, and the direction the weight then moves along.
+ * (Fig. 4a: exponential averages of the gradient and of its square, each divided by 1 - beta^t, and their
+ * quotient.  The second average decays with beta2 and gains with 1 - beta2; epsilon sits outside the root.) */
+typedef struct { double first_moment, second_moment, direction; } element_step;
+
+static element_step advance_element(const step_terms *k, double total, double weight, double first_moment,
+                                    double second_moment)
+{
+    element_step e;
+    double grad = total / k->grad_divisor;
+    if (k->decay_in_gradient) grad += k->decay * weight;
+    e.first_moment = k->beta1 * first_moment + (1.0 - k->beta1) * grad;
+    e.second_moment = k->beta2 * second_moment + (1.0 - k->beta2) * grad * grad;
+    const double mean = e.first_moment / k->unbias1;
+    const double spread = sqrt(e.second_moment / k->unbias2);
+    e.direction = mean / (spread + k->eps);
+    if (!k->decay_in_gradient) e.direction += k->decay * weight;
+    return e;
+}
+
+/* State is stored as fp32 (one rounding to nearest even), and the fp16 copy is made from the stored fp32 value. */
+static void store_weight(double weight_new, float *w_out, uint16_t *w16_out)
+{
+    *w_out = (float)weight_new;
+    *w16_out = oracle_float_to_half(*w_out);
+}
+
 /* ---- Adam on one tensor of the slice (Fig. 4a) ----
  * adam_mode 1: decoupled decay, u += wd*w.   adam_mode 0: L2, g += wd*w before the moments.
  * guard_elements != 0: an element whose reduced gradient is not finite keeps its inputs. */
@@ -129,35 +182,25 @@ void oracle_adam_tensor(uint64_t n, int R, const void *const *g, int grad_f32,
                         float loss_scale_f, int step, int grad_average, int adam_mode,
                         int guard_elements)
 {
-    const double lr = lr_f, beta1 = beta1_f, beta2 = beta2_f, eps = eps_f, wd = wd_f;
-    const double div = unscale_divisor(loss_scale_f, R, grad_average);
-    const double c1 = 1.0 - pow(beta1, (double)step);
-    const double c2 = 1.0 - pow(beta2, (double)step);
+    const step_terms k = make_step_terms(lr_f, beta1_f, beta2_f, eps_f, wd_f, loss_scale_f, step, R, grad_average,
+                                         adam_mode == 0);
     for (uint64_t i = 0; i < n; ++i) {
-        const double S = reduced_sum(g, grad_f32, R, i);
-        if (guard_elements && sum_overflows(S)) {
+        const double total = reduced_sum(g, grad_f32, R, i);
+        if (guard_elements && sum_overflows(total)) {
             w_out[i] = w[i]; m_out[i] = m[i]; v_out[i] = v[i];
             w16_out[i] = oracle_float_to_half(w[i]);
             continue;
         }
-        const double wi = w[i];
-        double gh = S / div;
-        if (adam_mode == 0) gh += wd * wi;
-        const double m_ = (double)m[i] * beta1 + (1.0 - beta1) * gh;
-        const double v_ = (double)v[i] * beta2 + (1.0 - beta2) * gh * gh;
-        const double m1 = m_ / c1;
-        const double v1 = v_ / c2;
-        double u = m1 / (sqrt(v1) + eps);
-        if (adam_mode != 0) u += wd * wi;
-        const double p_ = wi - lr * u;
-        m_out[i] = (float)m_;
-        v_out[i] = (float)v_;
-        w_out[i] = (float)p_;
-        w16_out[i] = oracle_float_to_half(w_out[i]);
+        const element_step e = advance_element(&k, total, w[i], m[i], v[i]);
+        m_out[i] = (float)e.first_moment;
+        v_out[i] = (float)e.second_moment;
+        store_weight((double)w[i] - k.lr * e.direction, &w_out[i], &w16_out[i]);
     }
 }
 
 /* ---- LAMB on one tensor of the slice ----
+ * The layerwise rule on top of the same moments: the whole tensor moves along u, scaled by ||w|| / ||u||, both
+ * norms over the pre-step weights and the directions of the elements this rank holds; a zero norm gives ratio 1.
  * Returns the two norms through norms[0] = ||w||, norms[1] = ||u|| (may be NULL). */
 void oracle_lamb_tensor(uint64_t n, int R, const void *const *g, int grad_f32,
                         const float *w, const float *m, const float *v,
@@ -165,34 +208,20 @@ void oracle_lamb_tensor(uint64_t n, int R, const void *const *g, int grad_f32,
                         float lr_f, float beta1_f, float beta2_f, float eps_f, float wd_f,
                         float loss_scale_f, int step, int grad_average, double *norms)
 {
-    const double lr = lr_f, beta1 = beta1_f, beta2 = beta2_f, eps = eps_f, wd = wd_f;
-    const double div = unscale_divisor(loss_scale_f, R, grad_average);
-    const double c1 = 1.0 - pow(beta1, (double)step);
-    const double c2 = 1.0 - pow(beta2, (double)step);
-    double sum_w2 = 0.0, sum_u2 = 0.0;
-    /* first sweep: moments, and the two sums of squares over this rank's elements */
-    for (uint64_t i = 0; i < n; ++i) {
-        const double gh = reduced_sum(g, grad_f32, R, i) / div;
-        const double wi = w[i];
-        const double m_ = (double)m[i] * beta1 + (1.0 - beta1) * gh;
-        const double v_ = (double)v[i] * beta2 + (1.0 - beta2) * gh * gh;
-        m_out[i] = (float)m_;
-        v_out[i] = (float)v_;
-        const double u = (m_ / c1) / (sqrt(v_ / c2) + eps) + wd * wi;
-        sum_w2 += wi * wi;
-        sum_u2 += u * u;
+    const step_terms k = make_step_terms(lr_f, beta1_f, beta2_f, eps_f, wd_f, loss_scale_f, step, R, grad_average, 0);
+    double weight_squares = 0.0, direction_squares = 0.0;
+    for (uint64_t i = 0; i < n; ++i) {                       /* the norm has to be known before any weight moves */
+        const element_step e = advance_element(&k, reduced_sum(g, grad_f32, R, i), w[i], m[i], v[i]);
+        m_out[i] = (float)e.first_moment;
+        v_out[i] = (float)e.second_moment;
+        weight_squares += (double)w[i] * (double)w[i];
+        direction_squares += e.direction * e.direction;
     }
-    const double norm_w = sqrt(sum_w2), norm_u = sqrt(sum_u2);
-    const double ratio = (norm_w > 0.0 && norm_u > 0.0) ? norm_w / norm_u : 1.0;
-    if (norms) { norms[0] = norm_w; norms[1] = norm_u; }
-    /* second sweep: the same u, scaled by the tensor's ratio */
+    const double weight_norm = sqrt(weight_squares), direction_norm = sqrt(direction_squares);
+    const double trust = (weight_norm > 0.0 && direction_norm > 0.0) ? weight_norm / direction_norm : 1.0;
+    if (norms) { norms[0] = weight_norm; norms[1] = direction_norm; }
     for (uint64_t i = 0; i < n; ++i) {
-        const double gh = reduced_sum(g, grad_f32, R, i) / div;
-        const double wi = w[i];
-        const double m_ = (double)m[i] * beta1 + (1.0 - beta1) * gh;
-        const double v_ = (double)v[i] * beta2 + (1.0 - beta2) * gh * gh;
-        const double u = (m_ / c1) / (sqrt(v_ / c2) + eps) + wd * wi;
-        w_out[i] = (float)(wi - lr * ratio * u);
-        w16_out[i] = oracle_float_to_half(w_out[i]);
+        const element_step e = advance_element(&k, reduced_sum(g, grad_f32, R, i), w[i], m[i], v[i]);
+        store_weight((double)w[i] - k.lr * trust * e.direction, &w_out[i], &w16_out[i]);
     }
 }

@@ -14,28 +14,36 @@ PIN_FILES = [os.path.join(ROOT, "tests", "test_oracle_pins.py"), os.path.join(RO
 
 # (name, text in oracle.c, replacement, which occurrence)
 MUTANTS = [
-    ("second moment uses beta1 rate", "(1.0 - beta2) * gh * gh", "(1.0 - beta1) * gh * gh", 0),
-    ("epsilon inside the root", "sqrt(v1) + eps", "sqrt(v1 + eps)", 0),
-    ("no first-moment bias correction", "const double m1 = m_ / c1;", "const double m1 = m_;", 0),
-    ("no second-moment bias correction", "const double v1 = v_ / c2;", "const double v1 = v_;", 0),
-    ("update sign", "const double p_ = wi - lr * u;", "const double p_ = wi + lr * u;", 0),
-    ("decoupled decay dropped", "if (adam_mode != 0) u += wd * wi;", "", 0),
-    ("L2 decay dropped", "if (adam_mode == 0) gh += wd * wi;", "", 0),
-    ("only the last rank is kept", "S += grad_f32 == 1 ?", "S = grad_f32 == 1 ?", 0),
-    ("fp32 slices read as halves", "grad_f32 == 1 ? (double)((const float *)g[r])[i]", "0 ? (double)((const float *)g[r])[i]", 0),
-    ("fp16 intermediate not rounded", "if (grad_f32 == 2) S = oracle_half_to_double(oracle_float_to_half((float)S));", "", 0),
-    ("flag decided in double", "return !isfinite((float)S);", "return !isfinite(S);", 0),
-    ("step off by one", "pow(beta1, (double)step)", "pow(beta1, (double)(step + 1))", 0),
-    ("gradient not squared", "(double)v[i] * beta2 + (1.0 - beta2) * gh * gh;\n        const double m1", "(double)v[i] * beta2 + (1.0 - beta2) * gh;\n        const double m1", 0),
-    ("loss scale multiplies", "double gh = S / div;", "double gh = S * div;", 0),
+    ("second moment uses beta1 rate", "(1.0 - k->beta2) * grad * grad", "(1.0 - k->beta1) * grad * grad", 0),
+    ("second moment decays with beta1", "k->beta2 * second_moment", "k->beta1 * second_moment", 0),
+    ("epsilon inside the root", "const double spread = sqrt(e.second_moment / k->unbias2);\n    e.direction = mean / (spread + k->eps);",
+     "const double spread = sqrt(e.second_moment / k->unbias2 + k->eps);\n    e.direction = mean / spread;", 0),
+    ("no first-moment bias correction", "e.first_moment / k->unbias1", "e.first_moment", 0),
+    ("no second-moment bias correction", "e.second_moment / k->unbias2", "e.second_moment", 0),
+    ("update sign", "(double)w[i] - k.lr * e.direction", "(double)w[i] + k.lr * e.direction", 0),
+    ("decoupled decay dropped", "if (!k->decay_in_gradient) e.direction += k->decay * weight;", "", 0),
+    ("L2 decay dropped", "if (k->decay_in_gradient) grad += k->decay * weight;", "", 0),
+    ("decay modes swapped", "adam_mode == 0);", "adam_mode != 0);", 0),
+    ("only the last rank is kept", "total += kind == SLICES_F32 ?", "total = kind == SLICES_F32 ?", 0),
+    ("fp32 slices read as halves", "kind == SLICES_F32 ? (double)((const float *)slice[r])[i]", "0 ? (double)((const float *)slice[r])[i]", 0),
+    ("fp16 intermediate not rounded", "if (kind == SLICES_F16_SUM_F16) total = oracle_half_to_double(oracle_float_to_half((float)total));", "", 0),
+    ("flag decided in double", "return !isfinite((float)total);", "return !isfinite(total);", 0),
+    ("step off by one", "pow(k.beta1, (double)step)", "pow(k.beta1, (double)(step + 1))", 0),
+    ("second bias correction from beta1", "pow(k.beta2, (double)step)", "pow(k.beta1, (double)step)", 0),
+    ("gradient not squared", "(1.0 - k->beta2) * grad * grad", "(1.0 - k->beta2) * grad", 0),
+    ("loss scale multiplies", "double grad = total / k->grad_divisor;", "double grad = total * k->grad_divisor;", 0),
     ("average ignored", "(grad_average ? (double)R : 1.0)", "1.0", 0),
-    ("flag ignores infinities", "return !isfinite((float)S);", "return isnan((float)S);", 0),
-    ("guard keeps nothing", "if (guard_elements && sum_overflows(S)) {", "if (0) {", 0),
-    ("trust ratio inverted", "norm_w / norm_u : 1.0", "norm_u / norm_w : 1.0", 0),
-    ("trust ratio fallback", "norm_w / norm_u : 1.0", "norm_w / norm_u : 0.0", 0),
-    ("norm of u without decay", "+ eps) + wd * wi;\n        sum_w2", "+ eps);\n        sum_w2", 0),
-    ("LAMB applies no ratio", "wi - lr * ratio * u", "wi - lr * u", 0),
-    ("LAMB second moment rate", "(1.0 - beta2) * gh * gh", "(1.0 - beta1) * gh * gh", 2),
+    ("flag ignores infinities", "return !isfinite((float)total);", "return isnan((float)total);", 0),
+    ("guard keeps nothing", "if (guard_elements && sum_overflows(total)) {", "if (0) {", 0),
+    ("state not rounded to fp32 before the fp16 copy", "*w16_out = oracle_float_to_half(*w_out);", "*w16_out = oracle_double_to_half(weight_new);", 0),
+    ("trust ratio inverted", "weight_norm / direction_norm : 1.0", "direction_norm / weight_norm : 1.0", 0),
+    ("trust ratio fallback", "weight_norm / direction_norm : 1.0", "weight_norm / direction_norm : 0.0", 0),
+    ("LAMB takes L2 decay", "step, R, grad_average, 0);", "step, R, grad_average, 1);", 0),
+    ("LAMB applies no ratio", "k.lr * trust * e.direction", "k.lr * e.direction", 0),
+    ("weight norm not squared", "weight_squares += (double)w[i] * (double)w[i];", "weight_squares += fabs((double)w[i]);", 0),
+    ("direction norm without the root", "direction_norm = sqrt(direction_squares)", "direction_norm = direction_squares", 0),
+    ("LAMB moments not stored", "m_out[i] = (float)e.first_moment;\n        v_out[i] = (float)e.second_moment;\n        weight_squares",
+     "m_out[i] = m[i];\n        v_out[i] = v[i];\n        weight_squares", 0),
     ("half subnormal scale", "ldexp((double)frac, -24)", "ldexp((double)frac, -25)", 0),
     ("half exponent bias", "expo - 25", "expo - 24", 0),
     ("half encode rounds ties up", "nearbyint(ldexp(fr, 11))", "floor(ldexp(fr, 11) + 0.5)", 0),

@@ -137,6 +137,36 @@ def test_first_step_is_lr_times_sign_up_to_eps():
     assert np.all(np.abs(delta + lr * np.sign(S)) <= bound + 1e-12)
 
 
+def test_fp16_copy_is_made_from_the_stored_fp32_weight():
+    """State is fp32 and the fp16 copy is what a cast of that fp32 tensor gives (two roundings, not one).
+    Worked by hand: the first step with m = v = 0, no decay and eps = 0 moves w by exactly lr sign(S).  With
+    w = 1 + 2^-10 and lr = 2^-11 - 2^-30 the exact result is T + 2^-30, T = 1 + 2^-11 being the midpoint of the fp16
+    neighbours 1 and 1 + 2^-10.  fp32 has no room for the 2^-30: the stored weight is T itself, and the tie goes
+    to the even fp16 neighbour 1.0 (0x3C00).  Rounding the exact result to fp16 directly would give 1 + 2^-10."""
+    w = np.array([1 + 2.0 ** -10, -(1 + 2.0 ** -10)], np.float32)
+    grads = [half_bits([0.25, -0.25])]
+    lr = 2.0 ** -11 - 2.0 ** -30
+    assert float(np.float32(lr)) == lr
+    ot = make_tensor(w, grads, wd=0.0)
+    oracle.adam_step([ot], Hyper(lr=lr, eps=0.0, step=1))
+    assert np.array_equal(ot.w_out, np.array([1 + 2.0 ** -11, -(1 + 2.0 ** -11)], np.float32))
+    assert list(ot.w16_out) == [0x3C00, 0xBC00]
+    # LAMB on a one-element tensor: ratio = |w| / |sign| = |w|, so the move is lr |w| sign(S); w = 1 gives the same numbers
+    # when lr is chosen for it: 1 - lr' = T' + tiny with T' = 1 - 2^-12 the midpoint of fp16's 1 - 2^-11 and 1
+    lr2 = 2.0 ** -12 - 2.0 ** -32
+    assert float(np.float32(lr2)) == lr2
+    ot = make_tensor(np.array([1.0], np.float32), [half_bits([0.5])], wd=0.0)
+    oracle.lamb_step([ot], Hyper(lr=lr2, eps=0.0, step=1))
+    assert ot.w_out[0] == np.float32(1 - 2.0 ** -12)          # 1 - 2^-12 + 2^-32 does not fit fp32 below 1 (ulp 2^-24)
+    assert ot.w16_out[0] == 0x3C00                              # tie between 0x3BFF and 0x3C00: even is 0x3C00; direct rounding gives 0x3C00 too
+    # the mirrored case separates the two roundings for LAMB as well: exact = T' - 2^-32 -> fp32 T' -> tie -> 0x3C00, direct -> 0x3BFF
+    lr3 = 2.0 ** -12 + 2.0 ** -32
+    assert float(np.float32(lr3)) == lr3
+    ot = make_tensor(np.array([1.0], np.float32), [half_bits([0.5])], wd=0.0)
+    oracle.lamb_step([ot], Hyper(lr=lr3, eps=0.0, step=1))
+    assert ot.w_out[0] == np.float32(1 - 2.0 ** -12) and ot.w16_out[0] == 0x3C00
+
+
 def test_identical_gradients_sum_to_R_times_g():
     rng = np.random.default_rng(3)
     n, R = 1000, 8
