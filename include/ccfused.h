@@ -19,8 +19,9 @@
  *   - Every call returns CC_OK (0) or a negative cc_status; nothing throws.  cc_last_error() gives a
  *     thread-local message for the last failing call on this thread.
  *   - Step calls are asynchronous: they enqueue kernels on `hip_stream` (a hipStream_t passed as
- *     void*, NULL = the default stream) and never synchronise.  Arguments are validated on the host
- *     before anything is enqueued; a rejected call enqueues nothing.
+ *     void*, NULL = the default stream); they never synchronise and never allocate, so every step
+ *     call can be captured into a HIP graph.  Arguments are validated on the host before anything
+ *     is enqueued; a rejected call enqueues nothing.
  *   - A plan may be used by one stream at a time: its scratch buffers are shared by all of its calls.
  */
 #ifndef CCFUSED_H
@@ -36,7 +37,7 @@ extern "C" {
 #endif
 
 #define CC_MAX_R 16            /* most gradient slices one element can be reduced from */
-#define CC_VERSION 100
+#define CC_VERSION 200
 
 typedef enum cc_status {
     CC_OK = 0,
@@ -52,8 +53,10 @@ typedef enum cc_status {
  * One tensor of the shard (the p, g, m, v of Fig. 4, restricted to this rank's slice).
  * All pointers are device pointers to `numel` elements and must be 16-byte aligned (numel == 0:
  * pointers are ignored).  w/m/v outputs may be the same buffers as the inputs (in place) or
- * different ones (out of place, so that a skipped step leaves the inputs untouched); partial
- * overlap is an error.  Only grad[0..R-1] are read.
+ * different ones (out of place, so that a skipped step leaves the inputs untouched).  Any other
+ * overlap that involves an output is an error (CC_ERR_ALIAS), within a tensor and across the
+ * tensors of a plan: two output buffers, or an output with w_in/m_in/v_in/grad[r] other than its
+ * own in-place input.  Inputs may overlap inputs.  Only grad[0..R-1] are read.
  */
 typedef struct cc_tensor {
     uint64_t        numel;
@@ -113,7 +116,7 @@ int64_t cc_ordered_table_fill(const uint64_t *numels, int32_t T, int32_t chunk_e
                               uint32_t *table, int64_t capacity, int64_t *full_chunks);
 
 /* Default chunk size in elements for large shards (a tuning choice of this library; the paper's buckets hold
- * 2^10).  Shards below 64 Mi elements default to 1024-element chunks (faster there in the size sweep). */
+ * 2^10, Section 5.4).  Shards below 64 Mi elements default to 1024-element chunks (faster there in the size sweep). */
 int32_t cc_default_chunk_elems(void);
 
 /* ---- plan ---- */
@@ -121,8 +124,10 @@ int32_t cc_default_chunk_elems(void);
 /*
  * Validates the T tensors (host array, copied) and builds the device-side descriptor array and chunk
  * table once, like the paper's wrapper pre-computes bucket pointers (Section 5.5).  R = number of
- * gradient slices per tensor, 1..CC_MAX_R.  chunk_elems: 0 = default, else a positive multiple of 1024 up to 2^24
- * (chunks of 4096 and more run in 512-thread workgroups, smaller ones in 128-thread workgroups).
+ * gradient slices per tensor, 1..CC_MAX_R.  chunk_elems: a positive multiple of 1024 up to 2^24 (chunks of 4096
+ * and more run in 512-thread workgroups, smaller ones in 128-thread workgroups), or 0: the plan is then prepared for
+ * chunks of 1024, 4096 and 16384 elements (8 bytes of table per chunk each), starts with the one the size rule picks
+ * (1024 below 64 Mi elements, else 4096), and cc_plan_set_chunk_elems / cc_plan_autotune can switch between them.
  * The plan owns only its own tables and scratch; it keeps raw copies of the caller's pointers, which
  * must stay valid while the plan is used.  Tensors with numel == 0 are legal and produce no chunks.
  */
@@ -134,9 +139,9 @@ int cc_plan_create_ex(const cc_tensor *tensors, int32_t T, int32_t R, int32_t ch
 int cc_plan_destroy(cc_plan *plan);
 
 /*
- * How a plan's kernels are laid over the device (a tuning choice like the paper's autotuner picking protocol and
- * channels, Section 5.3; results do not depend on it beyond the order of LAMB's per-chunk partial sums, which
- * both schedules keep identical).
+ * How a plan's kernels are laid over the device (a tuning choice like the protocol and the number of channels that
+ * the paper's standalone experiments sweep, Section 6.1.1; results do not depend on it beyond the order of LAMB's
+ * per-chunk partial sums, which both schedules keep identical).
  *   CC_SCHEDULE_PER_CHUNK  one workgroup per chunk, launched as a grid of that many workgroups.
  *   CC_SCHEDULE_ORDERED    `workgroups` persistent workgroups (0 = one per compute unit) take the chunks in table
  *                          order from a counter and keep the next chunk's loads in flight; needs the default
@@ -149,10 +154,29 @@ int cc_plan_set_schedule(cc_plan *plan, int32_t schedule, int32_t workgroups);
 int cc_plan_schedule(const cc_plan *plan, int32_t *schedule, int32_t *workgroups);
 
 /*
- * Picks the schedule by measurement instead of by the size rule, as the paper's autotuner keeps the fastest
- * configuration per workload (Section 5.3): runs the plan's own fused step (optimizer 0 = Adam, 1 = LAMB) a few
- * times under each candidate (one workgroup per chunk; ordered with compute units / 2, x 1 and x 2 workgroups, if the
- * plan's chunk size allows it), timed with events on `hip_stream`, and leaves the plan set to the fastest.  The
+ * Chunk size of the step calls: one of the sizes the plan was prepared for (see cc_plan_create), or 0 for the size
+ * rule.  Adam results do not depend on it; LAMB's norms are summed chunk by chunk, so they move in the last bits.
+ * cc_plan_layout reports what the plan will use (each pointer may be NULL): chunk size, threads per workgroup,
+ * cache policy (CC_CACHE_STREAMING or CC_CACHE_RESIDENT).
+ */
+int cc_plan_set_chunk_elems(cc_plan *plan, int32_t chunk_elems);
+int cc_plan_layout(const cc_plan *plan, int32_t *chunk_elems, int32_t *block_threads, int32_t *cache_policy);
+
+/*
+ * Cache policy of the streaming kernels' accesses.  STREAMING marks every access non-temporal (right for shards
+ * that do not fit on chip).  RESIDENT uses plain accesses, so that a shard whose whole step fits the 256 MB Infinity
+ * Cache finds its inputs on chip in the next step; it exists for 128-thread workgroups (chunks below 4096 elements)
+ * and is ignored otherwise.  AUTO (default) picks RESIDENT when the step's buffers total less than 192 MiB.
+ */
+typedef enum cc_cache_policy { CC_CACHE_AUTO = 0, CC_CACHE_STREAMING = 1, CC_CACHE_RESIDENT = 2 } cc_cache_policy;
+int cc_plan_set_cache_policy(cc_plan *plan, int32_t policy);
+
+/*
+ * Picks chunk size, workgroup size, cache policy, schedule and workgroup count by measurement instead of by the size
+ * rule, as the paper's autotuner keeps the fastest schedule per workload (Section 3.5): runs the plan's own fused
+ * step (optimizer 0 = Adam, 1 = LAMB) a few times under each candidate (one workgroup per chunk for every chunk size
+ * the plan was prepared for, with both cache policies where they exist; ordered with compute units / 2, x 1 and x 2
+ * workgroups on the 4096-element chunks), timed with events on `hip_stream`, and leaves the plan set to the fastest.  The
  * trial steps are ordinary steps on the caller's buffers: they write the out buffers and the flag, never the in
  * buffers, so the plan must be out of place (CC_ERR_ALIAS otherwise) and the caller must not have adopted the out
  * buffers' contents.  Synchronises the stream.  best_ms / per_chunk_ms (each may be NULL) receive the time per step
@@ -200,10 +224,13 @@ int cc_lamb_norms_read(cc_plan *plan, double *h_sums, void *hip_stream);
 
 /*
  * Same results as the fused calls, computed by separate kernels with the reduced gradient stored to and
- * re-read from an fp32 buffer owned by the plan (allocated on first use): reduce R slices -> fp32,
- * optimizer kernel(s) on the reduced gradient, fp32 -> fp16 cast.  The flag is known after the reduce
- * kernel, so in skip_mode 0 the later kernels leave every output untouched on overflow.
+ * re-read from an fp32 buffer owned by the plan: reduce R slices -> fp32, optimizer kernel(s) on the reduced
+ * gradient, fp32 -> fp16 cast.  The flag is known after the reduce kernel, so in skip_mode 0 the later kernels
+ * leave every output untouched on overflow.
+ * cc_plan_reserve_unfused allocates that buffer (4 bytes per element; synchronous; once per plan, further calls do
+ * nothing).  The unfused step calls return CC_ERR_ARG until it has been called: a step call never allocates.
  */
+int cc_plan_reserve_unfused(cc_plan *plan);
 int cc_unfused_adam_step(cc_plan *plan, const cc_hparams *hp, int32_t *d_overflow_flag, void *hip_stream);
 int cc_unfused_lamb_step(cc_plan *plan, const cc_hparams *hp, int32_t *d_overflow_flag, void *hip_stream);
 
@@ -239,6 +266,11 @@ typedef struct cc_epilogue {
     uint16_t       *out;                   /* numel fp16 */
     float           dropout_p;
     uint64_t        seed;
+    void           *workspace;             /* NULL, or 256 bytes of device memory (256-byte aligned) that are zero before
+                                              the first call and that every call leaves zero: slices of 4 Mi elements and
+                                              more then run under the ordered persistent schedule (cc_plan_set_schedule).
+                                              Calls that share a workspace must not overlap in time.  Ignored by
+                                              cc_unfused_epilogue. */
 } cc_epilogue;
 
 /* One pass: 2R + 4 bytes per element. */
@@ -253,6 +285,18 @@ int cc_unfused_epilogue(const cc_epilogue *args, float *d_sum_scratch, void *hip
 /* Plain streaming copy of `bytes` (multiple of 16, both pointers 16-byte aligned) device to device with
  * the same launch shape as the fused kernels; gives the practical HBM ceiling and calibrates counters. */
 int cc_copy_probe(void *d_dst, const void *d_src, uint64_t bytes, void *hip_stream);
+
+/* The memory pattern of the small-shard fused Adam step on one tensor (R = 4 or 8 fp16 slices, numel a multiple of
+ * 1024, one 128-thread workgroup per 1024 elements) with parts taken away, to show where a launch-bound step's time
+ * goes: what = 0 empty workgroups, 1 the loads only, 2 the stores only (w_out, m_out, v_out, w16_out receive filler
+ * values), 3 loads and stores without the update arithmetic and without the flag (outputs are not an Adam step).
+ * cache_policy: CC_CACHE_STREAMING or CC_CACHE_RESIDENT.  d_sink: one device int32 (never written in practice). */
+int cc_pattern_probe(const cc_tensor *tensor, int32_t R, int32_t what, int32_t cache_policy, int32_t *d_sink,
+                     void *hip_stream);
+
+/* Waits for `hip_stream`, then reads the ordered schedule's ticket counter and finished-workgroup word of the plan
+ * (both are zero between launches; a test aid). */
+int cc_plan_queue_state(cc_plan *plan, uint32_t *next_ticket, uint64_t *done_word, void *hip_stream);
 
 /* What the current device reports about itself (any output pointer may be NULL): compute units, memory clock in
  * kHz and memory bus width in bits as hipDeviceGetAttribute gives them, total device memory in bytes. */

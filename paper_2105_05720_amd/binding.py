@@ -13,6 +13,7 @@ from typing import List, Optional, Sequence
 CC_MAX_R = 16
 CC_GRAD_F16, CC_GRAD_F32 = 0, 1
 CC_SCHEDULE_AUTO, CC_SCHEDULE_PER_CHUNK, CC_SCHEDULE_ORDERED = 0, 1, 2
+CC_CACHE_AUTO, CC_CACHE_STREAMING, CC_CACHE_RESIDENT = 0, 1, 2
 CC_OK, CC_ERR_NULL, CC_ERR_ARG, CC_ERR_ALIGN, CC_ERR_ALIAS, CC_ERR_HIP, CC_ERR_NOMEM = 0, -1, -2, -3, -4, -5, -6
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -44,7 +45,7 @@ class cc_hparams(C.Structure):
 class cc_epilogue(C.Structure):
     _fields_ = [("numel", C.c_uint64), ("first", C.c_uint64), ("hidden", C.c_uint32), ("R", C.c_int32),
                 ("partial", C.c_void_p * CC_MAX_R), ("bias", C.c_void_p), ("residual", C.c_void_p), ("out", C.c_void_p),
-                ("dropout_p", C.c_float), ("seed", C.c_uint64)]
+                ("dropout_p", C.c_float), ("seed", C.c_uint64), ("workspace", C.c_void_p)]
 
 
 # every symbol include/ccfused.h declares
@@ -59,6 +60,11 @@ EXPORTS = {
     "cc_plan_destroy": (C.c_int, [C.c_void_p]),
     "cc_plan_set_schedule": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32]),
     "cc_plan_schedule": (C.c_int, [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
+    "cc_plan_set_chunk_elems": (C.c_int, [C.c_void_p, C.c_int32]),
+    "cc_plan_layout": (C.c_int, [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
+    "cc_plan_set_cache_policy": (C.c_int, [C.c_void_p, C.c_int32]),
+    "cc_plan_reserve_unfused": (C.c_int, [C.c_void_p]),
+    "cc_plan_queue_state": (C.c_int, [C.c_void_p, C.POINTER(C.c_uint32), C.POINTER(C.c_uint64), C.c_void_p]),
     "cc_plan_autotune": (C.c_int, [C.c_void_p, C.POINTER(cc_hparams), C.c_int32, C.c_void_p, C.c_void_p,
                                    C.POINTER(C.c_float), C.POINTER(C.c_float)]),
     "cc_plan_info": (C.c_int, [C.c_void_p, C.POINTER(C.c_uint64), C.POINTER(C.c_int64), C.POINTER(C.c_uint64)]),
@@ -73,6 +79,7 @@ EXPORTS = {
     "cc_unfused_lamb_step": (C.c_int, [C.c_void_p, C.POINTER(cc_hparams), C.c_void_p, C.c_void_p]),
     "cc_fused_epilogue": (C.c_int, [C.POINTER(cc_epilogue), C.c_void_p]),
     "cc_unfused_epilogue": (C.c_int, [C.POINTER(cc_epilogue), C.c_void_p, C.c_void_p]),
+    "cc_pattern_probe": (C.c_int, [C.POINTER(cc_tensor), C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]),
     "cc_copy_probe": (C.c_int, [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]),
     "cc_device_info": (C.c_int, [C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_uint64)]),
     "cc_last_error": (C.c_char_p, []),
@@ -213,14 +220,7 @@ def cc_plan_create(tensors: Sequence[Tensor], R: int, chunk_elems: int = 0) -> P
 def cc_plan_create_ex(tensors: Sequence[Tensor], R: int, chunk_elems: int = 0, grad_dtype: int = CC_GRAD_F16) -> Plan:
     arr = (cc_tensor * max(len(tensors), 1))()
     for i, t in enumerate(tensors):
-        c = arr[i]
-        c.numel = t.numel
-        c.w_in, c.m_in, c.v_in = _ptr(t.w_in), _ptr(t.m_in), _ptr(t.v_in)
-        c.w_out, c.m_out, c.v_out = _ptr(t.w_out), _ptr(t.m_out), _ptr(t.v_out)
-        c.w16_out = _ptr(t.w16_out)
-        for r, g in enumerate(t.grad[:CC_MAX_R]):
-            c.grad[r] = _ptr(g)
-        c.weight_decay = t.weight_decay
+        arr[i] = _c_tensor(t)
     handle = C.c_void_p()
     _check(load().cc_plan_create_ex(arr, len(tensors), R, chunk_elems, grad_dtype, C.byref(handle)))
     return Plan(handle.value, list(tensors))
@@ -241,9 +241,35 @@ def cc_plan_schedule(plan: Plan):
     return sched.value, wgs.value
 
 
+def cc_plan_set_chunk_elems(plan: Plan, chunk_elems: int = 0) -> None:
+    _check(load().cc_plan_set_chunk_elems(plan.handle, chunk_elems))
+
+
+def cc_plan_layout(plan: Plan):
+    """(chunk size in elements, threads per workgroup, CC_CACHE_STREAMING or CC_CACHE_RESIDENT) the plan will use."""
+    ce, blk, pol = C.c_int32(), C.c_int32(), C.c_int32()
+    _check(load().cc_plan_layout(plan.handle, C.byref(ce), C.byref(blk), C.byref(pol)))
+    return ce.value, blk.value, pol.value
+
+
+def cc_plan_set_cache_policy(plan: Plan, policy: int = CC_CACHE_AUTO) -> None:
+    _check(load().cc_plan_set_cache_policy(plan.handle, policy))
+
+
+def cc_plan_reserve_unfused(plan: Plan) -> None:
+    _check(load().cc_plan_reserve_unfused(plan.handle))
+
+
+def cc_plan_queue_state(plan: Plan, stream=None):
+    """(ticket counter, finished-workgroup word) of the ordered schedule after waiting for the stream; both 0 between launches."""
+    nxt, done = C.c_uint32(), C.c_uint64()
+    _check(load().cc_plan_queue_state(plan.handle, C.byref(nxt), C.byref(done), _stream(stream)))
+    return nxt.value, done.value
+
+
 def cc_plan_autotune(plan: Plan, hp, flag, optimizer: int = 0, stream=None):
-    """Times the candidate schedules on the plan's own buffers and keeps the fastest.  Returns (ms per step of the
-    schedule kept, ms per step with one workgroup per chunk)."""
+    """Times the candidate layouts and schedules on the plan's own buffers and keeps the fastest.  Returns (ms per step
+    of what was kept, ms per step with one workgroup per chunk under the layout the plan had)."""
     c = _hp(hp)
     best, per_chunk = C.c_float(), C.c_float()
     _check(load().cc_plan_autotune(plan.handle, C.byref(c), optimizer, _ptr(flag), _stream(stream), C.byref(best), C.byref(per_chunk)))
@@ -305,7 +331,8 @@ def cc_lamb_norms_read(plan: Plan, T: int, stream=None):
     return [(buf[2 * i], buf[2 * i + 1]) for i in range(T)]
 
 
-def _epilogue(partials, bias, residual, out, first: int, hidden: int, dropout_p: float, seed: int, numel=None) -> cc_epilogue:
+def _epilogue(partials, bias, residual, out, first: int, hidden: int, dropout_p: float, seed: int, numel=None,
+              workspace=None) -> cc_epilogue:
     e = cc_epilogue()
     e.numel = residual.numel() if numel is None else numel
     e.first, e.hidden, e.R = first, hidden, len(partials)
@@ -313,12 +340,13 @@ def _epilogue(partials, bias, residual, out, first: int, hidden: int, dropout_p:
         e.partial[r] = _ptr(x)
     e.bias, e.residual, e.out = _ptr(bias), _ptr(residual), _ptr(out)
     e.dropout_p, e.seed = dropout_p, seed
+    e.workspace = _ptr(workspace)
     return e
 
 
 def cc_fused_epilogue(partials, bias, residual, out, first: int, hidden: int, dropout_p: float, seed: int, stream=None,
-                      numel=None) -> None:
-    e = _epilogue(partials, bias, residual, out, first, hidden, dropout_p, seed, numel)
+                      numel=None, workspace=None) -> None:
+    e = _epilogue(partials, bias, residual, out, first, hidden, dropout_p, seed, numel, workspace)
     _check(load().cc_fused_epilogue(C.byref(e), _stream(stream)))
 
 
@@ -326,6 +354,23 @@ def cc_unfused_epilogue(partials, bias, residual, out, sum_scratch, first: int, 
                         stream=None, numel=None) -> None:
     e = _epilogue(partials, bias, residual, out, first, hidden, dropout_p, seed, numel)
     _check(load().cc_unfused_epilogue(C.byref(e), _ptr(sum_scratch), _stream(stream)))
+
+
+def _c_tensor(t: Tensor) -> cc_tensor:
+    c = cc_tensor()
+    c.numel = t.numel
+    c.w_in, c.m_in, c.v_in = _ptr(t.w_in), _ptr(t.m_in), _ptr(t.v_in)
+    c.w_out, c.m_out, c.v_out = _ptr(t.w_out), _ptr(t.m_out), _ptr(t.v_out)
+    c.w16_out = _ptr(t.w16_out)
+    for r, g in enumerate(t.grad[:CC_MAX_R]):
+        c.grad[r] = _ptr(g)
+    c.weight_decay = t.weight_decay
+    return c
+
+
+def cc_pattern_probe(tensor: Tensor, R: int, what: int, cache_policy: int, sink, stream=None) -> None:
+    c = _c_tensor(tensor)
+    _check(load().cc_pattern_probe(C.byref(c), R, what, cache_policy, _ptr(sink), _stream(stream)))
 
 
 def cc_copy_probe(dst, src, nbytes: int, stream=None) -> None:

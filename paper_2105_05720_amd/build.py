@@ -23,6 +23,10 @@ FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fvisibility=hidden",
     "-ffp-contract=off",                                              # fused multiply-adds are written out by hand
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",      # no packed-fp32 instructions
+    # The kernels issue their counting atomics (flag count, chunk ticket) early and look at the result a block of work
+    # later.  The compiler's wave-level atomic aggregation would rewrite each into "one lane adds, readfirstlane the
+    # result", which needs the result at once and so drains the wave's memory counter right behind the atomic.
+    "-mllvm", "-amdgpu-atomic-optimizer-strategy=None",
     "-Wall", "-Wextra", "-Wno-unused-parameter",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
 ]

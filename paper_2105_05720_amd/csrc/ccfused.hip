@@ -2,6 +2,7 @@
 // Everything that touches a parameter runs in the kernels of kernels.hip.h; nothing here computes an update.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -50,26 +51,96 @@ int32_t resolve_chunk(int32_t chunk_elems, uint64_t total_elems = ~0ull)
 
 bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
-// 0: disjoint, 1: identical, -1: partial overlap
-int overlap(const void *a, const void *b, uint64_t bytes)
+// One buffer of one tensor, for the overlap check of a plan.
+struct Span {
+    uintptr_t begin, end;
+    int32_t tensor;
+    int8_t kind;        // 0..2: w, m, v (in or out), 3: w16_out, 4: a gradient slice
+    bool output;
+};
+
+const char *span_name(const Span &x)
 {
-    const uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b);
-    if (x == y) return 1;
-    if (x + bytes <= y || y + bytes <= x) return 0;
-    return -1;
+    static const char *in_names[5] = {"w_in", "m_in", "v_in", "?", "grad"}, *out_names[4] = {"w_out", "m_out", "v_out", "w16_out"};
+    return x.output ? out_names[x.kind] : in_names[x.kind];
 }
 
-}  // namespace
+// Rejects every overlap that involves an output buffer, within a tensor and across tensors, except an input that is
+// exactly its own output (in place).  Sorting the buffers by start address makes one pass enough: an overlapping pair
+// shows when the later one starts before the furthest end seen so far in the class it may not touch.
+int check_overlaps(const cc_tensor *tensors, int32_t T, int32_t R, size_t grad_bytes, bool *in_place)
+{
+    std::vector<Span> spans;
+    *in_place = false;
+    try {
+        spans.reserve((size_t)T * (size_t)(7 + R));
+        for (int32_t t = 0; t < T; ++t) {
+            const cc_tensor &x = tensors[t];
+            if (x.numel == 0) continue;
+            const void *ins[3] = {x.w_in, x.m_in, x.v_in};
+            void *outs[3] = {x.w_out, x.m_out, x.v_out};
+            for (int k = 0; k < 3; ++k) {
+                const uintptr_t o = reinterpret_cast<uintptr_t>(outs[k]), i = reinterpret_cast<uintptr_t>(ins[k]);
+                spans.push_back(Span{o, o + x.numel * 4, t, (int8_t)k, true});
+                if (i == o) *in_place = true;                       // the input IS the output: one buffer
+                else spans.push_back(Span{i, i + x.numel * 4, t, (int8_t)k, false});
+            }
+            const uintptr_t h = reinterpret_cast<uintptr_t>(x.w16_out);
+            spans.push_back(Span{h, h + x.numel * 2, t, 3, true});
+            for (int r = 0; r < R; ++r) {
+                const uintptr_t g = reinterpret_cast<uintptr_t>(x.grad[r]);
+                spans.push_back(Span{g, g + x.numel * grad_bytes, t, 4, false});
+            }
+        }
+        std::sort(spans.begin(), spans.end(), [](const Span &a, const Span &b) { return a.begin < b.begin; });
+    } catch (const std::bad_alloc &) {
+        return fail(CC_ERR_NOMEM, "cc_plan_create: out of host memory");
+    }
+    const Span *far_out = nullptr, *far_in = nullptr;           // the output / input seen so far that ends last
+    for (const Span &x : spans) {
+        const Span *hit = nullptr;
+        if (far_out && x.begin < far_out->end) hit = far_out;
+        else if (x.output && far_in && x.begin < far_in->end) hit = far_in;
+        if (hit)
+            return fail(CC_ERR_ALIAS, "tensor %d %s overlaps tensor %d %s (only an input that is exactly its own output may share memory with an output)",
+                        x.tensor, span_name(x), hit->tensor, span_name(*hit));
+        if (x.output) { if (!far_out || x.end > far_out->end) far_out = &x; }
+        else if (!far_in || x.end > far_in->end) far_in = &x;
+    }
+    return CC_OK;
+}
 
-namespace {
+// Buffers a step touches: R gradient slices, both copies of w, m, v (one if in place) and the fp16 weights.
+uint64_t step_footprint_bytes(const cc_plan *p)
+{
+    return p->numel * ((p->grad_f32 ? 4u : 2u) * (uint64_t)p->R + 12u + 14u);
+}
 
+// Settles what the step calls will use (layout, schedule, cache policy) from what the caller asked for.
 void resolve_schedule(cc_plan *p)
 {
+    int want = p->chunk_choice;
+    if (want == 0) want = p->numel < kSmallShardElems ? kSmallChunkElems : kDefaultChunkElems;
+    p->active = 0;
+    for (size_t i = 0; i < p->layouts.size(); ++i)
+        if (p->layouts[i].chunk_elems == want) p->active = (int)i;
+    const Layout &L = p->lay();
     if (p->schedule == CC_SCHEDULE_ORDERED) p->ordered = true;
     else if (p->schedule == CC_SCHEDULE_PER_CHUNK) p->ordered = false;
-    else p->ordered = p->chunk_elems == kDefaultChunkElems && p->chunks >= kOrderedMinChunksPerCu * (int64_t)p->cus &&
-                      !(p->grad_f32 && p->R > kOrderedMaxF32Slices);
-    if (p->chunk_elems != kDefaultChunkElems || p->chunks == 0) p->ordered = false;
+    else p->ordered = L.chunks >= kOrderedMinChunksPerCu * (int64_t)p->cus && !(p->grad_f32 && p->R > kOrderedMaxF32Slices);
+    if (L.chunk_elems != kDefaultChunkElems || L.chunks == 0) p->ordered = false;
+    if (p->cache_policy == CC_CACHE_RESIDENT) p->resident = true;
+    else if (p->cache_policy == CC_CACHE_STREAMING) p->resident = false;
+    else p->resident = step_footprint_bytes(p) < kResidentMaxBytes;
+    if (L.block != kSmallBlock || p->ordered) p->resident = false;
+}
+
+void free_layout(Layout &L)
+{
+    if (L.d_tensors) (void)hipFree(L.d_tensors);
+    if (L.d_chunks) (void)hipFree(L.d_chunks);
+    if (L.d_chunks_ordered) (void)hipFree(L.d_chunks_ordered);
+    L.d_tensors = nullptr; L.d_chunks = nullptr; L.d_chunks_ordered = nullptr;
 }
 
 }  // namespace
@@ -151,16 +222,17 @@ int cc_plan_create_ex(const cc_tensor *tensors, int32_t T, int32_t R, int32_t ch
     if (R < 1 || R > CC_MAX_R) return fail(CC_ERR_ARG, "cc_plan_create: R = %d outside 1..%d", R, CC_MAX_R);
     if (grad_dtype != CC_GRAD_F16 && grad_dtype != CC_GRAD_F32) return fail(CC_ERR_ARG, "cc_plan_create: grad_dtype = %d", grad_dtype);
     if (resolve_chunk(chunk_elems) < 0) return fail(CC_ERR_ARG, "chunk_elems = %d is not a positive multiple of 1024 up to 2^24", chunk_elems);
-    uint64_t total_elems = 0;
-    for (int32_t t = 0; t < T; ++t) total_elems += tensors[t].numel;
-    const int32_t ce = resolve_chunk(chunk_elems, total_elems);
-
-    bool in_place = false;
-    std::vector<uint64_t> numels((size_t)T);
+    std::vector<uint64_t> numels;
+    try {
+        numels.resize((size_t)T);
+    } catch (const std::bad_alloc &) {
+        return fail(CC_ERR_NOMEM, "cc_plan_create: out of host memory");
+    }
     for (int32_t t = 0; t < T; ++t) {
         const cc_tensor &x = tensors[t];
         numels[(size_t)t] = x.numel;
         if (x.numel == 0) continue;
+        if (x.numel > (1ull << 40)) return fail(CC_ERR_ARG, "tensor %d: numel = %llu exceeds 2^40", t, (unsigned long long)x.numel);
         if (!std::isfinite(x.weight_decay)) return fail(CC_ERR_ARG, "tensor %d: weight_decay is not finite", t);
         const void *ptrs[7] = {x.w_in, x.m_in, x.v_in, x.w_out, x.m_out, x.v_out, x.w16_out};
         static const char *names[7] = {"w_in", "m_in", "v_in", "w_out", "m_out", "v_out", "w16_out"};
@@ -172,68 +244,50 @@ int cc_plan_create_ex(const cc_tensor *tensors, int32_t T, int32_t R, int32_t ch
             if (!x.grad[r]) return fail(CC_ERR_NULL, "tensor %d: grad[%d] is NULL", t, r);
             if (misaligned(x.grad[r])) return fail(CC_ERR_ALIGN, "tensor %d: grad[%d] is not 16-byte aligned", t, r);
         }
-        const uint64_t bytes = x.numel * 4;
-        const int ow = overlap(x.w_in, x.w_out, bytes), om = overlap(x.m_in, x.m_out, bytes), ov = overlap(x.v_in, x.v_out, bytes);
-        if (ow < 0 || om < 0 || ov < 0) return fail(CC_ERR_ALIAS, "tensor %d: in and out buffers overlap partially", t);
-        in_place = in_place || ow || om || ov;
     }
-    const int64_t chunks = cc_chunk_count(numels.data(), T, ce);
-    if (chunks < 0) return (int)chunks;
+    bool in_place = false;
+    {
+        const int rc = check_overlaps(tensors, T, R, grad_dtype == CC_GRAD_F32 ? 4u : 2u, &in_place);
+        if (rc) return rc;
+    }
+    // chunk sizes the plan is prepared for: the caller's, or the three the tuner chooses among (a size whose table
+    // would not fit one launch is left out)
+    int32_t sizes[3];
+    int nsizes = 0;
+    if (chunk_elems != 0) {
+        const int64_t c = cc_chunk_count(numels.data(), T, chunk_elems);
+        if (c < 0) return (int)c;
+        sizes[nsizes++] = chunk_elems;
+    } else {
+        for (int32_t ce : {kSmallChunkElems, kDefaultChunkElems, kLargeChunkElems})
+            if (cc_chunk_count(numels.data(), T, ce) >= 0) sizes[nsizes++] = ce;
+        if (nsizes == 0) return (int)cc_chunk_count(numels.data(), T, kLargeChunkElems);     // leaves the message
+    }
 
     cc_plan *p = new (std::nothrow) cc_plan;
     if (!p) return fail(CC_ERR_NOMEM, "cc_plan_create: out of host memory");
-    p->T = T; p->R = R; p->chunk_elems = ce; p->chunks = chunks; p->in_place = in_place;
-    p->block = ce >= kDefaultChunkElems ? kBigBlock : kSmallBlock;
+    p->T = T; p->R = R; p->in_place = in_place; p->chunk_choice = chunk_elems;
     p->grad_f32 = grad_dtype == CC_GRAD_F32;
-    std::vector<uint32_t> table;
     try {
-        p->host_tensors.resize((size_t)T);
         p->gsum_offset.resize((size_t)T);
-        table.resize((size_t)(2 * chunks) + 2);
+        p->layouts.resize((size_t)nsizes);
+        for (int i = 0; i < nsizes; ++i) p->layouts[(size_t)i].host_tensors.resize((size_t)T);
     } catch (const std::bad_alloc &) {
         delete p;
         return fail(CC_ERR_NOMEM, "cc_plan_create: out of host memory");
     }
-    uint64_t first = 0, goff = 0, total = 0;
-    for (int32_t t = 0; t < T; ++t) {
-        const cc_tensor &x = tensors[t];
-        DevTensor &d = p->host_tensors[(size_t)t];
-        std::memset(&d, 0, sizeof(d));
-        d.numel = x.numel;
-        d.w_in = x.w_in; d.m_in = x.m_in; d.v_in = x.v_in;
-        d.w_out = x.w_out; d.m_out = x.m_out; d.v_out = x.v_out;
-        d.w16 = x.w16_out;
-        for (int r = 0; r < R; ++r) d.grad[r] = x.grad[r];
-        d.wd = x.weight_decay;
-        d.first_chunk = (uint32_t)first;
-        d.num_chunks = (uint32_t)((x.numel + (uint64_t)ce - 1) / (uint64_t)ce);
-        first += d.num_chunks;
-        p->gsum_offset[(size_t)t] = goff;
-        goff += (x.numel + 7) / 8 * 8;            // every tensor starts 32-byte aligned in the fp32 buffer
-        total += x.numel;
-    }
-    p->numel = total;
-    p->gsum_elems = goff;
     {
+        uint64_t goff = 0, total = 0;
         int32_t nonempty = 0;
-        for (int32_t t = 0; t < T; ++t)
+        for (int32_t t = 0; t < T; ++t) {
+            p->gsum_offset[(size_t)t] = goff;
+            goff += (tensors[t].numel + 7) / 8 * 8;            // every tensor starts 32-byte aligned in the fp32 buffer
+            total += tensors[t].numel;
             if (tensors[t].numel > 0) { ++nonempty; p->single = t; }
+        }
         if (nonempty != 1) p->single = -1;
-    }
-    cc_chunk_table_fill(numels.data(), T, ce, table.data(), chunks);
-    // The ordered schedule's table: the same entries, full chunks first (tensor order = address order inside each
-    // arena), then the short last chunks, which take the unpipelined path.
-    std::vector<uint32_t> ordered_table;
-    try {
-        ordered_table.resize((size_t)(2 * chunks) + 2);
-    } catch (const std::bad_alloc &) {
-        delete p;
-        return fail(CC_ERR_NOMEM, "cc_plan_create: out of host memory");
-    }
-    {
-        int64_t nfull = 0;
-        cc_ordered_table_fill(numels.data(), T, ce, ordered_table.data(), chunks, &nfull);
-        p->nfull = (uint32_t)nfull;
+        p->numel = total;
+        p->gsum_elems = goff;
     }
 
 #define PLAN_TRY(expr)                                                                             \
@@ -245,17 +299,56 @@ int cc_plan_create_ex(const cc_tensor *tensors, int32_t T, int32_t R, int32_t ch
             return CC_ERR_HIP;                                                                     \
         }                                                                                          \
     } while (0)
-    PLAN_TRY(hipMalloc((void **)&p->d_tensors, sizeof(DevTensor) * (size_t)T));
-    PLAN_TRY(hipMemcpy(p->d_tensors, p->host_tensors.data(), sizeof(DevTensor) * (size_t)T, hipMemcpyHostToDevice));
-    PLAN_TRY(hipMalloc((void **)&p->d_chunks, sizeof(Chunk) * (size_t)(chunks + 1)));
-    if (chunks > 0) PLAN_TRY(hipMemcpy(p->d_chunks, table.data(), sizeof(Chunk) * (size_t)chunks, hipMemcpyHostToDevice));
-    PLAN_TRY(hipMalloc((void **)&p->d_partials, sizeof(double) * 2 * (size_t)(chunks + 1)));
+    int64_t most_chunks = 0;
+    for (int i = 0; i < nsizes; ++i) {
+        Layout &L = p->layouts[(size_t)i];
+        const int32_t ce = sizes[i];
+        L.chunk_elems = ce;
+        L.block = ce >= kDefaultChunkElems ? kBigBlock : kSmallBlock;
+        L.chunks = cc_chunk_count(numels.data(), T, ce);
+        if (L.chunks > most_chunks) most_chunks = L.chunks;
+        uint64_t first = 0;
+        for (int32_t t = 0; t < T; ++t) {
+            const cc_tensor &x = tensors[t];
+            DevTensor &d = L.host_tensors[(size_t)t];
+            std::memset(&d, 0, sizeof(d));
+            d.numel = x.numel;
+            d.w_in = x.w_in; d.m_in = x.m_in; d.v_in = x.v_in;
+            d.w_out = x.w_out; d.m_out = x.m_out; d.v_out = x.v_out;
+            d.w16 = x.w16_out;
+            for (int r = 0; r < R; ++r) d.grad[r] = x.grad[r];
+            d.wd = x.weight_decay;
+            d.first_chunk = (uint32_t)first;
+            d.num_chunks = (uint32_t)((x.numel + (uint64_t)ce - 1) / (uint64_t)ce);
+            first += d.num_chunks;
+        }
+        std::vector<uint32_t> table;
+        try {
+            table.resize((size_t)(2 * L.chunks) + 2);
+        } catch (const std::bad_alloc &) {
+            cc_plan_destroy(p);
+            return fail(CC_ERR_NOMEM, "cc_plan_create: out of host memory");
+        }
+        PLAN_TRY(hipMalloc((void **)&L.d_tensors, sizeof(DevTensor) * (size_t)T));
+        PLAN_TRY(hipMemcpy(L.d_tensors, L.host_tensors.data(), sizeof(DevTensor) * (size_t)T, hipMemcpyHostToDevice));
+        cc_chunk_table_fill(numels.data(), T, ce, table.data(), L.chunks);
+        PLAN_TRY(hipMalloc((void **)&L.d_chunks, sizeof(Chunk) * (size_t)(L.chunks + 1)));
+        if (L.chunks > 0) PLAN_TRY(hipMemcpy(L.d_chunks, table.data(), sizeof(Chunk) * (size_t)L.chunks, hipMemcpyHostToDevice));
+        if (ce == kDefaultChunkElems) {
+            // The ordered schedule's table: the same entries, full chunks first (tensor order = address order inside
+            // each arena), then the short last chunks, which take the unpipelined path.
+            int64_t nfull = 0;
+            cc_ordered_table_fill(numels.data(), T, ce, table.data(), L.chunks, &nfull);
+            L.nfull = (uint32_t)nfull;
+            PLAN_TRY(hipMalloc((void **)&L.d_chunks_ordered, sizeof(Chunk) * (size_t)(L.chunks + 1)));
+            if (L.chunks > 0) PLAN_TRY(hipMemcpy(L.d_chunks_ordered, table.data(), sizeof(Chunk) * (size_t)L.chunks, hipMemcpyHostToDevice));
+        }
+    }
+    PLAN_TRY(hipMalloc((void **)&p->d_partials, sizeof(double) * 2 * (size_t)(most_chunks + 1)));
     PLAN_TRY(hipMalloc((void **)&p->d_sums, sizeof(double) * 2 * (size_t)T));
     PLAN_TRY(hipMemset(p->d_sums, 0, sizeof(double) * 2 * (size_t)T));
     PLAN_TRY(hipMalloc((void **)&p->d_flag_scratch, sizeof(FlagScratch)));
     PLAN_TRY(hipMemset(p->d_flag_scratch, 0, sizeof(FlagScratch)));
-    PLAN_TRY(hipMalloc((void **)&p->d_chunks_ordered, sizeof(Chunk) * (size_t)(chunks + 1)));
-    if (chunks > 0) PLAN_TRY(hipMemcpy(p->d_chunks_ordered, ordered_table.data(), sizeof(Chunk) * (size_t)chunks, hipMemcpyHostToDevice));
     PLAN_TRY(hipMalloc((void **)&p->d_queue, sizeof(WorkQueue)));
     PLAN_TRY(hipMemset(p->d_queue, 0, sizeof(WorkQueue)));
     {
@@ -276,11 +369,74 @@ int cc_plan_set_schedule(cc_plan *p, int32_t schedule, int32_t workgroups)
     if (schedule != CC_SCHEDULE_AUTO && schedule != CC_SCHEDULE_PER_CHUNK && schedule != CC_SCHEDULE_ORDERED)
         return fail(CC_ERR_ARG, "cc_plan_set_schedule: schedule = %d", schedule);
     if (workgroups < 0 || workgroups > 65536) return fail(CC_ERR_ARG, "cc_plan_set_schedule: workgroups = %d outside 0..65536", workgroups);
-    if (schedule == CC_SCHEDULE_ORDERED && p->chunk_elems != kDefaultChunkElems)
-        return fail(CC_ERR_ARG, "the ordered schedule needs chunk_elems = %d (plan has %d)", kDefaultChunkElems, p->chunk_elems);
+    if (schedule == CC_SCHEDULE_ORDERED && p->lay().chunk_elems != kDefaultChunkElems)
+        return fail(CC_ERR_ARG, "the ordered schedule needs chunk_elems = %d (plan uses %d)", kDefaultChunkElems, p->lay().chunk_elems);
     p->schedule = schedule;
     p->ordered_grid = (unsigned)workgroups;
     resolve_schedule(p);
+    return CC_OK;
+}
+
+int cc_plan_set_chunk_elems(cc_plan *p, int32_t chunk_elems)
+{
+    if (!p) return fail(CC_ERR_NULL, "cc_plan_set_chunk_elems: plan is NULL");
+    if (chunk_elems != 0) {
+        bool have = false;
+        for (const Layout &L : p->layouts) have = have || L.chunk_elems == chunk_elems;
+        if (!have) return fail(CC_ERR_ARG, "cc_plan_set_chunk_elems: the plan was not prepared for chunks of %d elements", chunk_elems);
+        if (p->schedule == CC_SCHEDULE_ORDERED && chunk_elems != kDefaultChunkElems)
+            return fail(CC_ERR_ARG, "the ordered schedule needs chunk_elems = %d", kDefaultChunkElems);
+    }
+    p->chunk_choice = chunk_elems;
+    resolve_schedule(p);
+    return CC_OK;
+}
+
+int cc_plan_layout(const cc_plan *p, int32_t *chunk_elems, int32_t *block_threads, int32_t *cache_policy)
+{
+    if (!p) return fail(CC_ERR_NULL, "cc_plan_layout: plan is NULL");
+    if (chunk_elems) *chunk_elems = p->lay().chunk_elems;
+    if (block_threads) *block_threads = p->lay().block;
+    if (cache_policy) *cache_policy = p->resident ? CC_CACHE_RESIDENT : CC_CACHE_STREAMING;
+    return CC_OK;
+}
+
+int cc_plan_set_cache_policy(cc_plan *p, int32_t policy)
+{
+    if (!p) return fail(CC_ERR_NULL, "cc_plan_set_cache_policy: plan is NULL");
+    if (policy != CC_CACHE_AUTO && policy != CC_CACHE_STREAMING && policy != CC_CACHE_RESIDENT)
+        return fail(CC_ERR_ARG, "cc_plan_set_cache_policy: policy = %d", policy);
+    p->cache_policy = policy;
+    resolve_schedule(p);
+    return CC_OK;
+}
+
+int cc_plan_reserve_unfused(cc_plan *p)
+{
+    if (!p) return fail(CC_ERR_NULL, "cc_plan_reserve_unfused: plan is NULL");
+    if (p->d_gsum) return CC_OK;
+    float *buf = nullptr;
+    HIP_TRY(hipMalloc((void **)&buf, sizeof(float) * (size_t)(p->gsum_elems + 8)));
+    for (Layout &L : p->layouts) {
+        for (int32_t t = 0; t < p->T; ++t) L.host_tensors[(size_t)t].gsum = buf + p->gsum_offset[(size_t)t];
+        const hipError_t e = hipMemcpy(L.d_tensors, L.host_tensors.data(), sizeof(DevTensor) * (size_t)p->T, hipMemcpyHostToDevice);
+        if (e != hipSuccess) {
+            (void)hipFree(buf);
+            return fail(CC_ERR_HIP, "cc_plan_reserve_unfused: %s", hipGetErrorString(e));
+        }
+    }
+    p->d_gsum = buf;
+    return CC_OK;
+}
+
+int cc_plan_queue_state(cc_plan *p, uint32_t *next_ticket, uint64_t *done_word, void *stream)
+{
+    if (!p) return fail(CC_ERR_NULL, "cc_plan_queue_state: plan is NULL");
+    HIP_TRY(hipStreamSynchronize((hipStream_t)stream));
+    WorkQueue q;
+    HIP_TRY(hipMemcpy(&q, p->d_queue, sizeof(q), hipMemcpyDeviceToHost));
+    if (next_ticket) *next_ticket = q.next.v;
+    if (done_word) *done_word = q.done.v;
     return CC_OK;
 }
 
@@ -288,20 +444,18 @@ int cc_plan_schedule(const cc_plan *p, int32_t *schedule, int32_t *workgroups)
 {
     if (!p) return fail(CC_ERR_NULL, "cc_plan_schedule: plan is NULL");
     if (schedule) *schedule = p->ordered ? CC_SCHEDULE_ORDERED : CC_SCHEDULE_PER_CHUNK;
-    if (workgroups) *workgroups = p->ordered ? (int32_t)ordered_grid(p) : (int32_t)p->chunks;
+    if (workgroups) *workgroups = p->ordered ? (int32_t)ordered_grid(p) : (int32_t)p->chunks();
     return CC_OK;
 }
 
 int cc_plan_destroy(cc_plan *p)
 {
     if (!p) return CC_OK;
-    if (p->d_tensors) (void)hipFree(p->d_tensors);
-    if (p->d_chunks) (void)hipFree(p->d_chunks);
+    for (Layout &L : p->layouts) free_layout(L);
     if (p->d_partials) (void)hipFree(p->d_partials);
     if (p->d_sums) (void)hipFree(p->d_sums);
     if (p->d_gsum) (void)hipFree(p->d_gsum);
     if (p->d_flag_scratch) (void)hipFree(p->d_flag_scratch);
-    if (p->d_chunks_ordered) (void)hipFree(p->d_chunks_ordered);
     if (p->d_queue) (void)hipFree(p->d_queue);
     delete p;
     return CC_OK;
@@ -311,8 +465,8 @@ int cc_plan_info(const cc_plan *p, uint64_t *numel, int64_t *chunks, uint64_t *t
 {
     if (!p) return fail(CC_ERR_NULL, "cc_plan_info: plan is NULL");
     if (numel) *numel = p->numel;
-    if (chunks) *chunks = p->chunks;
-    if (table_bytes) *table_bytes = sizeof(Chunk) * (uint64_t)p->chunks + sizeof(DevTensor) * (uint64_t)p->T;   // of the schedule in use
+    if (chunks) *chunks = p->chunks();
+    if (table_bytes) *table_bytes = sizeof(Chunk) * (uint64_t)p->chunks() + sizeof(DevTensor) * (uint64_t)p->T;   // of the layout and schedule in use
     return CC_OK;
 }
 
@@ -366,18 +520,15 @@ int check_step(const cc_plan *p, const cc_hparams *hp, const void *flag, Opt opt
     s->eps = hp->eps;
     s->lr = hp->lr;
     s->inv_div = (float)(1.0 / ((double)hp->loss_scale * (hp->grad_average ? (double)p->R : 1.0)));
-    s->chunk_elems = (uint32_t)p->chunk_elems;
+    s->chunk_elems = (uint32_t)p->lay().chunk_elems;
     return CC_OK;
 }
 
-// Allocates the fp32 reduced-gradient buffer of the unfused pipelines and points every descriptor at it.
-int ensure_gsum(cc_plan *p)
+// The unfused pipelines need the plan's fp32 reduced-gradient buffer; a step call does not allocate it.
+int ensure_gsum(const cc_plan *p)
 {
     if (p->d_gsum) return CC_OK;
-    HIP_TRY(hipMalloc((void **)&p->d_gsum, sizeof(float) * (size_t)(p->gsum_elems + 8)));
-    for (int32_t t = 0; t < p->T; ++t) p->host_tensors[(size_t)t].gsum = p->d_gsum + p->gsum_offset[(size_t)t];
-    HIP_TRY(hipMemcpy(p->d_tensors, p->host_tensors.data(), sizeof(DevTensor) * (size_t)p->T, hipMemcpyHostToDevice));
-    return CC_OK;
+    return fail(CC_ERR_ARG, "the unfused pipelines need cc_plan_reserve_unfused(plan) first: step calls never allocate");
 }
 
 }  // namespace
@@ -390,7 +541,7 @@ int cc_fused_adam_step(cc_plan *p, const cc_hparams *hp, int32_t *flag, void *st
     int rc = check_step(p, hp, flag, Opt::Adam, &s);
     if (rc) return rc;
     hipStream_t st = (hipStream_t)stream;
-    if (p->chunks == 0) return clear_flag(flag, st);
+    if (p->chunks() == 0) return clear_flag(flag, st);
     const int mode = (hp->skip_mode == 1 ? kModeGuard : 0) | (hp->adam_mode == 0 ? kModeL2 : 0);
     if (p->grad_f32) launch_fused_adam_f32(p, s, flag, st, mode);
     else launch_fused_adam_f16(p, s, flag, st, mode);
@@ -403,7 +554,7 @@ int cc_fused_lamb_phase1(cc_plan *p, const cc_hparams *hp, int32_t *flag, void *
     int rc = check_step(p, hp, flag, Opt::Lamb, &s);
     if (rc) return rc;
     hipStream_t st = (hipStream_t)stream;
-    if (p->chunks == 0) {
+    if (p->chunks() == 0) {
         if ((rc = clear_flag(flag, st))) return rc;
     } else {
         launch_lamb_phase1(p, s, flag, st);
@@ -442,7 +593,7 @@ int cc_unfused_adam_step_ex(cc_plan *p, const cc_hparams *hp, int32_t *flag, voi
     if (sum16 && p->grad_f32) return fail(CC_ERR_ARG, "an fp16 intermediate needs fp16 gradient slices");
     if ((rc = ensure_gsum(p))) return rc;
     hipStream_t st = (hipStream_t)stream;
-    if (p->chunks == 0) return clear_flag(flag, st);
+    if (p->chunks() == 0) return clear_flag(flag, st);
     if (sum16) launch_reduce_half(p, s, flag, st);
     else launch_reduce(p, s, flag, st);
     if ((rc = launched("reduce_kernel"))) return rc;
@@ -459,7 +610,7 @@ int cc_unfused_lamb_step(cc_plan *p, const cc_hparams *hp, int32_t *flag, void *
     if (rc) return rc;
     if ((rc = ensure_gsum(p))) return rc;
     hipStream_t st = (hipStream_t)stream;
-    if (p->chunks == 0) {
+    if (p->chunks() == 0) {
         if ((rc = clear_flag(flag, st))) return rc;
         return lamb_norms(p, st);
     }
@@ -504,6 +655,8 @@ int check_epilogue(const cc_epilogue *e, EpilogueArgs *a)
 }
 
 constexpr int kEpilogueBlock = 512;
+constexpr uint32_t kEpilogueChunk = kEpilogueBlock * 8 * 2;
+constexpr uint64_t kEpilogueOrderedMinElems = 4u << 20;     // below this the ordered schedule's fixed latency does not pay
 
 int epilogue_grid(uint64_t numel, uint32_t chunk, unsigned *grid)
 {
@@ -522,8 +675,25 @@ int cc_fused_epilogue(const cc_epilogue *e, void *stream)
     if (rc) return rc;
     if (e->numel == 0) return CC_OK;
     unsigned grid;
-    if ((rc = epilogue_grid(e->numel, kEpilogueBlock * 8 * 2, &grid))) return rc;
+    if ((rc = epilogue_grid(e->numel, kEpilogueChunk, &grid))) return rc;
     hipStream_t st = (hipStream_t)stream;
+    if (e->workspace && (reinterpret_cast<uintptr_t>(e->workspace) & 255u) != 0)
+        return fail(CC_ERR_ALIGN, "epilogue: workspace is not 256-byte aligned");
+    if (e->workspace && e->numel >= kEpilogueOrderedMinElems) {
+        int dev = 0, cus = 0;
+        HIP_TRY(hipGetDevice(&dev));
+        HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+        unsigned wgs = cus > 0 ? (unsigned)cus : 1u;
+        if (wgs > (grid + 1) / 2) wgs = (grid + 1) / 2;
+        const uint32_t nfull = (uint32_t)(e->numel / kEpilogueChunk);
+        WorkQueue *q = (WorkQueue *)e->workspace;
+        switch (e->R) {
+#define CASE(r) case r: hipLaunchKernelGGL((fused_epilogue_ordered_kernel<r, kEpilogueBlock>), dim3(wgs), dim3(kEpilogueBlock), 0, st, a, nfull, grid, 1u, q); break;
+            FOR_EACH_R(CASE)
+#undef CASE
+        }
+        return launched("fused_epilogue_ordered_kernel");
+    }
     switch (e->R) {
 #define CASE(r) case r: hipLaunchKernelGGL((fused_epilogue_kernel<r, kEpilogueBlock>), dim3(grid), dim3(kEpilogueBlock), 0, st, a); break;
         FOR_EACH_R(CASE)
@@ -566,25 +736,40 @@ int cc_plan_autotune(cc_plan *p, const cc_hparams *hp, int32_t optimizer, int32_
         if (rc) return rc;
     }
     hipStream_t st = (hipStream_t)stream;
-    const int32_t keep_schedule = p->schedule;
-    const unsigned keep_grid = p->ordered_grid;
-    struct Candidate { int32_t schedule; unsigned workgroups; };
-    Candidate cand[4] = {{CC_SCHEDULE_PER_CHUNK, 0u}, {0, 0u}, {0, 0u}, {0, 0u}};
-    int n = 1;
-    if (p->chunk_elems == kDefaultChunkElems && p->chunks > 0) {
-        const unsigned cus = (unsigned)p->cus;
-        const unsigned tries[3] = {cus, cus > 1 ? cus / 2 : 1u, cus * 2};
-        for (unsigned w : tries) cand[n++] = Candidate{CC_SCHEDULE_ORDERED, w};
+    struct Candidate { int32_t chunk_elems, schedule; unsigned workgroups; int32_t cache; };
+    const Candidate keep{p->chunk_choice, p->schedule, p->ordered_grid, p->cache_policy};
+    // one workgroup per chunk under the plan's current layout first: its time is what per_chunk_ms reports
+    std::vector<Candidate> cand;
+    try {
+        const int32_t current = p->lay().chunk_elems;
+        cand.push_back(Candidate{current, CC_SCHEDULE_PER_CHUNK, 0u, CC_CACHE_STREAMING});
+        if (p->lay().block == kSmallBlock) cand.push_back(Candidate{current, CC_SCHEDULE_PER_CHUNK, 0u, CC_CACHE_RESIDENT});
+        for (const Layout &L : p->layouts) {
+            if (L.chunks == 0) continue;
+            if (L.chunk_elems != current) {
+                cand.push_back(Candidate{L.chunk_elems, CC_SCHEDULE_PER_CHUNK, 0u, CC_CACHE_STREAMING});
+                if (L.block == kSmallBlock) cand.push_back(Candidate{L.chunk_elems, CC_SCHEDULE_PER_CHUNK, 0u, CC_CACHE_RESIDENT});
+            }
+            if (L.chunk_elems == kDefaultChunkElems) {
+                const unsigned cus = (unsigned)p->cus;
+                for (unsigned w : {cus, cus > 1 ? cus / 2 : 1u, cus * 2}) cand.push_back(Candidate{L.chunk_elems, CC_SCHEDULE_ORDERED, w, CC_CACHE_STREAMING});
+            }
+        }
+    } catch (const std::bad_alloc &) {
+        return fail(CC_ERR_NOMEM, "cc_plan_autotune: out of host memory");
     }
     hipEvent_t e0 = nullptr, e1 = nullptr;
     HIP_TRY(hipEventCreate(&e0));
     if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return fail(CC_ERR_HIP, "hipEventCreate failed"); }
-    auto restore = [&](int32_t schedule, unsigned grid) { p->schedule = schedule; p->ordered_grid = grid; resolve_schedule(p); };
+    auto apply = [&](const Candidate &c) {
+        p->chunk_choice = c.chunk_elems; p->schedule = c.schedule; p->ordered_grid = c.workgroups; p->cache_policy = c.cache;
+        resolve_schedule(p);
+    };
     int rc = CC_OK, best = -1;
     float best_time = 0.f;
     constexpr int kTrials = 3;
-    for (int c = 0; c < n && rc == CC_OK; ++c) {
-        restore(cand[c].schedule, cand[c].workgroups);
+    for (size_t c = 0; c < cand.size() && rc == CC_OK; ++c) {
+        apply(cand[c]);
         float ms = 0.f;
         for (int i = 0; i <= kTrials && rc == CC_OK; ++i) {          // the first run warms up
             if (i == 1 && hipEventRecord(e0, st) != hipSuccess) rc = fail(CC_ERR_HIP, "hipEventRecord failed");
@@ -596,15 +781,15 @@ int cc_plan_autotune(cc_plan *p, const cc_hparams *hp, int32_t optimizer, int32_
         if (rc != CC_OK) break;
         ms /= (float)kTrials;
         if (c == 0 && per_chunk_ms) *per_chunk_ms = ms;
-        if (best < 0 || ms < best_time) { best = c; best_time = ms; }
+        if (best < 0 || ms < best_time) { best = (int)c; best_time = ms; }
     }
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);
     if (rc != CC_OK) {
-        restore(keep_schedule, keep_grid);
+        apply(keep);
         return rc;
     }
-    restore(cand[best].schedule, cand[best].workgroups);
+    apply(cand[(size_t)best]);
     if (best_ms) *best_ms = best_time;
     return CC_OK;
 }
@@ -622,6 +807,40 @@ int cc_device_info(int32_t *cus, int32_t *clock_khz, int32_t *bus_bits, uint64_t
         *total_bytes = (uint64_t)total_b;
     }
     return CC_OK;
+}
+
+int cc_pattern_probe(const cc_tensor *t, int32_t R, int32_t what, int32_t cache_policy, int32_t *d_sink, void *stream)
+{
+    if (!t || !d_sink) return fail(CC_ERR_NULL, "cc_pattern_probe: NULL argument");
+    if (R != 4 && R != 8) return fail(CC_ERR_ARG, "cc_pattern_probe: R = %d (4 or 8)", R);
+    if (what < 0 || what > 3) return fail(CC_ERR_ARG, "cc_pattern_probe: what = %d outside 0..3", what);
+    if (cache_policy != CC_CACHE_STREAMING && cache_policy != CC_CACHE_RESIDENT) return fail(CC_ERR_ARG, "cc_pattern_probe: cache_policy = %d", cache_policy);
+    if (t->numel == 0 || t->numel % kSmallChunkElems != 0 || t->numel / kSmallChunkElems > 0x7fffffffull)
+        return fail(CC_ERR_ARG, "cc_pattern_probe: numel = %llu must be a positive multiple of %d", (unsigned long long)t->numel, kSmallChunkElems);
+    const void *ptrs[7] = {t->w_in, t->m_in, t->v_in, t->w_out, t->m_out, t->v_out, t->w16_out};
+    for (const void *q : ptrs)
+        if (!q || misaligned(q)) return fail(CC_ERR_ALIGN, "cc_pattern_probe: a state pointer is NULL or not 16-byte aligned");
+    for (int r = 0; r < R; ++r)
+        if (!t->grad[r] || misaligned(t->grad[r])) return fail(CC_ERR_ALIGN, "cc_pattern_probe: grad[%d] is NULL or not 16-byte aligned", r);
+    DevTensor d;
+    std::memset(&d, 0, sizeof(d));
+    d.numel = t->numel;
+    d.w_in = t->w_in; d.m_in = t->m_in; d.v_in = t->v_in;
+    d.w_out = t->w_out; d.m_out = t->m_out; d.v_out = t->v_out;
+    d.w16 = t->w16_out;
+    for (int r = 0; r < R; ++r) d.grad[r] = t->grad[r];
+    StepScalars s;
+    std::memset(&s, 0, sizeof(s));
+    s.chunk_elems = (uint32_t)kSmallChunkElems;
+    const dim3 grid((unsigned)(t->numel / kSmallChunkElems)), block(kSmallBlock);
+    hipStream_t st = (hipStream_t)stream;
+#define PROBE(r, w, M) hipLaunchKernelGGL((pattern_probe_kernel<r, w, kSmallBlock, M>), grid, block, 0, st, d, s, d_sink)
+#define PROBE_W(r, M) switch (what) { case 0: PROBE(r, 0, M); break; case 1: PROBE(r, 1, M); break; case 2: PROBE(r, 2, M); break; default: PROBE(r, 3, M); break; }
+    if (cache_policy == CC_CACHE_RESIDENT) { if (R == 4) { PROBE_W(4, Resident) } else { PROBE_W(8, Resident) } }
+    else { if (R == 4) { PROBE_W(4, Streaming) } else { PROBE_W(8, Streaming) } }
+#undef PROBE_W
+#undef PROBE
+    return launched("pattern_probe_kernel");
 }
 
 int cc_copy_probe(void *dst, const void *src, uint64_t bytes, void *stream)

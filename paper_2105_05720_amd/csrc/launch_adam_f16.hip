@@ -1,55 +1,43 @@
-// Launches of the fused Adam kernels for fp16 gradient slices (every R, mode, schedule and workgroup size).
-#include "plan.hpp"
+// Launches of the fused Adam kernels for fp16 gradient slices.
+#include "launch_adam.inc.hpp"
 
 namespace ccf {
 
+void launch_fused_adam_f16(const cc_plan *p, const StepScalars &s, int32_t *flag, hipStream_t st, int mode)
+{
+    launch_fused_adam<false>(p, s, flag, st, mode);
+}
+
 namespace {
 
-template <int MODE, int BLK, bool GF32>
-void launch_fused_adam_r(const cc_plan *p, const StepScalars &s, int32_t *flag, hipStream_t st)
+template <int MODE, class MEM>
+void launch_flat_r(const DevTensor &t, int R, unsigned grid, const StepScalars &s, FlagScratch *fs, int32_t *flag, hipStream_t st)
 {
-    if (p->ordered) {
-        const dim3 grid(ordered_grid(p)), block(kBigBlock);
-        switch (p->R) {
-#define CASE(r) case r: hipLaunchKernelGGL((fused_adam_ordered_kernel<r, MODE, kBigBlock, GF32>), grid, block, 0, st, ORDERED_ARGS(p, kSpanAdam), s, p->d_queue, flag); break;
-            FOR_EACH_R(CASE)
-#undef CASE
-        }
-        return;
-    }
-    const dim3 grid((unsigned)p->chunks), block(BLK);
-    if (p->single >= 0) {                  // one tensor: no table, descriptor in the kernel arguments
-        const DevTensor &t = p->host_tensors[(size_t)p->single];
-        switch (p->R) {
-#define CASE(r) case r: hipLaunchKernelGGL((fused_adam_flat_kernel<r, MODE, BLK, GF32>), grid, block, 0, st, t, s, p->d_flag_scratch, flag); break;
-            FOR_EACH_R(CASE)
-#undef CASE
-        }
-        return;
-    }
-    switch (p->R) {
-#define CASE(r) case r: hipLaunchKernelGGL((fused_adam_kernel<r, MODE, BLK, GF32>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, p->d_flag_scratch, flag); break;
+    switch (R) {
+#define CASE(r) case r: hipLaunchKernelGGL((fused_adam_flat_kernel<r, MODE, kSmallBlock, false, 2, MEM>), dim3(grid), dim3(kSmallBlock), 0, st, t, s, fs, flag); break;
         FOR_EACH_R(CASE)
 #undef CASE
     }
 }
 
-template <int BLK, bool GF32>
-void launch_mode(const cc_plan *p, const StepScalars &s, int32_t *flag, hipStream_t st, int mode)
+template <class MEM>
+void launch_flat_mode(const DevTensor &t, int R, unsigned grid, const StepScalars &s, FlagScratch *fs, int32_t *flag, hipStream_t st, int mode)
 {
     switch (mode) {
-        case 0: launch_fused_adam_r<0, BLK, GF32>(p, s, flag, st); break;
-        case 1: launch_fused_adam_r<1, BLK, GF32>(p, s, flag, st); break;
-        case 2: launch_fused_adam_r<2, BLK, GF32>(p, s, flag, st); break;
-        default: launch_fused_adam_r<3, BLK, GF32>(p, s, flag, st); break;
+        case 0: launch_flat_r<0, MEM>(t, R, grid, s, fs, flag, st); break;
+        case 1: launch_flat_r<1, MEM>(t, R, grid, s, fs, flag, st); break;
+        case 2: launch_flat_r<2, MEM>(t, R, grid, s, fs, flag, st); break;
+        default: launch_flat_r<3, MEM>(t, R, grid, s, fs, flag, st); break;
     }
 }
 
 }  // namespace
 
-void launch_fused_adam_f16(const cc_plan *p, const StepScalars &s, int32_t *flag, hipStream_t st, int mode)
+void launch_fused_adam_flat_f16(const DevTensor &t, int R, unsigned grid, bool resident, const StepScalars &s, FlagScratch *fs,
+                                int32_t *flag, hipStream_t st, int mode)
 {
-    BY_BLOCK(p, (launch_mode<BLK, false>(p, s, flag, st, mode)));
+    if (resident) launch_flat_mode<Resident>(t, R, grid, s, fs, flag, st, mode);
+    else launch_flat_mode<Streaming>(t, R, grid, s, fs, flag, st, mode);
 }
 
 }  // namespace ccf

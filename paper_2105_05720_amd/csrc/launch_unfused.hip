@@ -5,9 +5,10 @@ namespace ccf {
 
 namespace {
 
-template <int BLK, bool GF32>
+template <int BLK, bool GF32, class MEM>
 void launch_reduce_r(const cc_plan *p, const StepScalars &s, int32_t *flag, hipStream_t st)
 {
+    const Layout &L = p->lay();
     if (p->ordered) {
         const dim3 grid(ordered_grid(p)), block(kBigBlock);
         switch (p->R) {
@@ -17,17 +18,18 @@ void launch_reduce_r(const cc_plan *p, const StepScalars &s, int32_t *flag, hipS
         }
         return;
     }
-    const dim3 grid((unsigned)p->chunks), block(BLK);
+    const dim3 grid((unsigned)L.chunks), block(BLK);
     switch (p->R) {
-#define CASE(r) case r: hipLaunchKernelGGL((reduce_kernel<r, BLK, GF32>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, p->d_flag_scratch, flag); break;
+#define CASE(r) case r: hipLaunchKernelGGL((reduce_kernel<r, BLK, GF32, MEM>), grid, block, 0, st, L.d_tensors, L.d_chunks, s, p->d_flag_scratch, flag); break;
         FOR_EACH_R(CASE)
 #undef CASE
     }
 }
 
-template <int BLK>
+template <int BLK, class MEM>
 void launch_reduce_half_b(const cc_plan *p, const StepScalars &s, int32_t *flag, hipStream_t st)
 {
+    const Layout &L = p->lay();
     if (p->ordered) {
         const dim3 grid(ordered_grid(p)), block(kBigBlock);
         switch (p->R) {
@@ -37,17 +39,18 @@ void launch_reduce_half_b(const cc_plan *p, const StepScalars &s, int32_t *flag,
         }
         return;
     }
-    const dim3 grid((unsigned)p->chunks), block(BLK);
+    const dim3 grid((unsigned)L.chunks), block(BLK);
     switch (p->R) {
-#define CASE(r) case r: hipLaunchKernelGGL((reduce_half_kernel<r, BLK>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, p->d_flag_scratch, flag); break;
+#define CASE(r) case r: hipLaunchKernelGGL((reduce_half_kernel<r, BLK, MEM>), grid, block, 0, st, L.d_tensors, L.d_chunks, s, p->d_flag_scratch, flag); break;
         FOR_EACH_R(CASE)
 #undef CASE
     }
 }
 
-template <int BLK, bool SUM16>
+template <int BLK, bool SUM16, class MEM>
 void launch_adam_from_sum_b(const cc_plan *p, const StepScalars &s, const int32_t *flag, hipStream_t st, int mode)
 {
+    const Layout &L = p->lay();
     if (p->ordered) {
         const dim3 grid(ordered_grid(p)), block(kBigBlock);
         switch (mode) {
@@ -58,12 +61,12 @@ void launch_adam_from_sum_b(const cc_plan *p, const StepScalars &s, const int32_
         }
         return;
     }
-    const dim3 grid((unsigned)p->chunks), block(BLK);
+    const dim3 grid((unsigned)L.chunks), block(BLK);
     switch (mode) {
-        case 0: hipLaunchKernelGGL((adam_from_sum_kernel<0, BLK, SUM16>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag); break;
-        case 1: hipLaunchKernelGGL((adam_from_sum_kernel<1, BLK, SUM16>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag); break;
-        case 2: hipLaunchKernelGGL((adam_from_sum_kernel<2, BLK, SUM16>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag); break;
-        default: hipLaunchKernelGGL((adam_from_sum_kernel<3, BLK, SUM16>), grid, block, 0, st, p->d_tensors, p->d_chunks, s, flag); break;
+        case 0: hipLaunchKernelGGL((adam_from_sum_kernel<0, BLK, SUM16, MEM>), grid, block, 0, st, L.d_tensors, L.d_chunks, s, flag); break;
+        case 1: hipLaunchKernelGGL((adam_from_sum_kernel<1, BLK, SUM16, MEM>), grid, block, 0, st, L.d_tensors, L.d_chunks, s, flag); break;
+        case 2: hipLaunchKernelGGL((adam_from_sum_kernel<2, BLK, SUM16, MEM>), grid, block, 0, st, L.d_tensors, L.d_chunks, s, flag); break;
+        default: hipLaunchKernelGGL((adam_from_sum_kernel<3, BLK, SUM16, MEM>), grid, block, 0, st, L.d_tensors, L.d_chunks, s, flag); break;
     }
 }
 
@@ -71,19 +74,19 @@ void launch_adam_from_sum_b(const cc_plan *p, const StepScalars &s, const int32_
 
 void launch_reduce(const cc_plan *p, const StepScalars &s, int32_t *flag, hipStream_t st)
 {
-    if (p->grad_f32) BY_BLOCK(p, (launch_reduce_r<BLK, true>(p, s, flag, st)));
-    else BY_BLOCK(p, (launch_reduce_r<BLK, false>(p, s, flag, st)));
+    if (p->grad_f32) BY_BLOCK(p, (launch_reduce_r<BLK, true, MEM>(p, s, flag, st)));
+    else BY_BLOCK(p, (launch_reduce_r<BLK, false, MEM>(p, s, flag, st)));
 }
 
 void launch_reduce_half(const cc_plan *p, const StepScalars &s, int32_t *flag, hipStream_t st)
 {
-    BY_BLOCK(p, launch_reduce_half_b<BLK>(p, s, flag, st));
+    BY_BLOCK(p, (launch_reduce_half_b<BLK, MEM>(p, s, flag, st)));
 }
 
 void launch_adam_from_sum(const cc_plan *p, const StepScalars &s, const int32_t *flag, hipStream_t st, int mode, bool sum16)
 {
-    if (sum16) BY_BLOCK(p, (launch_adam_from_sum_b<BLK, true>(p, s, flag, st, mode)));
-    else BY_BLOCK(p, (launch_adam_from_sum_b<BLK, false>(p, s, flag, st, mode)));
+    if (sum16) BY_BLOCK(p, (launch_adam_from_sum_b<BLK, true, MEM>(p, s, flag, st, mode)));
+    else BY_BLOCK(p, (launch_adam_from_sum_b<BLK, false, MEM>(p, s, flag, st, mode)));
 }
 
 // A plan without chunks launches no streaming kernel, so the flag is cleared by a one-thread kernel (a kernel
@@ -100,8 +103,8 @@ int cast_launch(cc_plan *p, const StepScalars &s, const int32_t *flag, hipStream
         hipLaunchKernelGGL((cast_ordered_kernel<kBigBlock>), dim3(ordered_grid(p)), dim3(kBigBlock), 0, st, ORDERED_ARGS(p, kSpanCast), s, p->d_queue, flag, guarded);
         return launched("cast_ordered_kernel");
     }
-    const dim3 grid((unsigned)p->chunks);
-    BY_BLOCK(p, hipLaunchKernelGGL((cast_kernel<BLK>), grid, dim3(BLK), 0, st, p->d_tensors, p->d_chunks, s, flag, guarded));
+    const dim3 grid((unsigned)p->chunks());
+    BY_BLOCK(p, hipLaunchKernelGGL((cast_kernel<BLK, MEM>), grid, dim3(BLK), 0, st, p->lay().d_tensors, p->lay().d_chunks, s, flag, guarded));
     return launched("cast_kernel");
 }
 

@@ -15,16 +15,33 @@ namespace ccf {
 
 constexpr int32_t kDefaultChunkElems = 4096;     // one sweep of a 512-thread workgroup (2 groups x 512 lanes x 4 elements)
 constexpr int32_t kSmallChunkElems = 1024;       // one sweep of a 128-thread workgroup: more workgroups for small shards
+constexpr int32_t kLargeChunkElems = 16384;      // four sweeps of a 512-thread workgroup: a quarter of the table and of the launches
 constexpr uint64_t kSmallShardElems = 64u << 20; // below this many elements the default chunk is the small one (size sweep)
 constexpr int32_t kMaxChunkElems = 1 << 24;      // lane offsets inside a chunk are 32-bit byte offsets
 constexpr int kBigBlock = 512, kSmallBlock = 128;
 constexpr int kOrderedMaxF32Slices = 4;           // fp32 slices: measured faster up to 4, slower at 8 (two chunks of 8 take 209 VGPRs)
 constexpr int64_t kOrderedMinChunksPerCu = 8;    // below this many chunks per compute unit a plan keeps one workgroup per chunk
+// A step whose buffers (R gradient slices, two copies of w, m, v and of the fp16 weights) stay below this many bytes
+// runs with plain instead of non-temporal accesses: it then lives in the 256 MB Infinity Cache from one step to the
+// next (size sweep: faster up to 2^22 elements at R = 8, slower from 2^23 on).
+constexpr uint64_t kResidentMaxBytes = 192u << 20;
 
 // Records the message for cc_last_error() on this thread and returns the code.
 int fail(cc_status code, const char *fmt, ...);
 // CC_OK, or CC_ERR_HIP with the runtime's message if the last launch failed.
 int launched(const char *what);
+
+// One chunking of a plan's tensor list: the table (Section 5.4) and the descriptors that go with it.
+struct Layout {
+    int32_t chunk_elems = 0;
+    int block = kBigBlock;                       // threads per workgroup of the streaming kernels
+    int64_t chunks = 0;
+    uint32_t nfull = 0;                          // full chunks; the ordered table lists them first, short last chunks behind
+    std::vector<DevTensor> host_tensors;         // host mirror of the device descriptors (first_chunk / num_chunks of this chunking)
+    DevTensor *d_tensors = nullptr;
+    Chunk *d_chunks = nullptr;                   // tensor order
+    Chunk *d_chunks_ordered = nullptr;           // the ordered schedule's order; only for kDefaultChunkElems
+};
 
 }  // namespace ccf
 
@@ -35,29 +52,30 @@ int launched(const char *what);
     } while (0)
 
 struct cc_plan {
-    int32_t T = 0, R = 0, chunk_elems = 0;
-    int block = ccf::kBigBlock;                  // threads per workgroup of the streaming kernels
-    ccf::FlagScratch *d_flag_scratch = nullptr;  // {done, bad}, zero between launches
+    int32_t T = 0, R = 0;
+    std::vector<ccf::Layout> layouts;       // one per chunk size the plan was prepared for
+    int active = 0;                         // the layout the step calls use
+    int32_t chunk_choice = 0;               // what the caller asked for (0 = the size rule)
+    ccf::FlagScratch *d_flag_scratch = nullptr;  // zero between launches
     bool ordered = false;                   // large shards: persistent workgroups take chunks in table order
     int32_t schedule = CC_SCHEDULE_AUTO;    // what the caller asked for
     unsigned ordered_grid = 0;              // workgroups of the ordered schedule (one per compute unit unless set)
+    bool resident = false;                  // plain instead of non-temporal accesses (small-chunk layout only)
+    int32_t cache_policy = CC_CACHE_AUTO;   // what the caller asked for
     int32_t cus = 0;                        // compute units of the device the plan was created on
     int32_t single = -1;                    // index of the only tensor with elements, or -1 if there are several (or none)
-    uint32_t nfull = 0;                     // full chunks; the ordered table lists them first, short last chunks behind
-    ccf::Chunk *d_chunks_ordered = nullptr;
-    ccf::WorkQueue *d_queue = nullptr;           // zero between launches
-    int64_t chunks = 0;
+    ccf::WorkQueue *d_queue = nullptr;      // zero between launches
     uint64_t numel = 0;
     bool in_place = false;                  // some tensor has out == in
     bool grad_f32 = false;                  // gradient slices are fp32 instead of fp16
-    std::vector<ccf::DevTensor> host_tensors;    // host mirror of the device descriptors
     std::vector<uint64_t> gsum_offset;      // element offset of each tensor in the unfused fp32 buffer
     uint64_t gsum_elems = 0;
-    ccf::DevTensor *d_tensors = nullptr;
-    ccf::Chunk *d_chunks = nullptr;
-    double *d_partials = nullptr;           // 2 per chunk (LAMB)
+    double *d_partials = nullptr;           // 2 per chunk of the finest layout (LAMB)
     double *d_sums = nullptr;               // 2 per tensor (LAMB)
-    float *d_gsum = nullptr;                // unfused pipelines, allocated on first use
+    float *d_gsum = nullptr;                // unfused pipelines: cc_plan_reserve_unfused
+
+    const ccf::Layout &lay() const { return layouts[(size_t)active]; }
+    int64_t chunks() const { return lay().chunks; }
 };
 
 namespace ccf {
@@ -67,18 +85,20 @@ namespace ccf {
 inline unsigned ordered_grid(const cc_plan *p)
 {
     unsigned g = p->ordered_grid ? p->ordered_grid : (unsigned)p->cus;
-    const unsigned most = (unsigned)((p->chunks + 1) / 2);
+    const unsigned most = (unsigned)((p->chunks() + 1) / 2);
     if (g > most) g = most;
     return g ? g : 1u;
 }
 
 #define FOR_EACH_R(X) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13) X(14) X(15) X(16)
 
-// Every streaming kernel exists for two workgroup sizes; the plan picks one from its chunk size.
-#define BY_BLOCK(p, CALL)                      \
-    do {                                       \
-        if ((p)->block == kBigBlock) { constexpr int BLK = kBigBlock; CALL; } \
-        else { constexpr int BLK = kSmallBlock; CALL; }                       \
+// Every per-chunk streaming kernel exists for two workgroup sizes, and the small one for both cache policies; the
+// plan's layout and residency pick one.  CALL sees BLK (int) and MEM (Streaming or Resident).
+#define BY_BLOCK(p, CALL)                                                                   \
+    do {                                                                                    \
+        if ((p)->lay().block == kBigBlock) { constexpr int BLK = kBigBlock; typedef Streaming MEM; CALL; }        \
+        else if ((p)->resident) { constexpr int BLK = kSmallBlock; typedef Resident MEM; CALL; }                   \
+        else { constexpr int BLK = kSmallBlock; typedef Streaming MEM; CALL; }                                    \
     } while (0)
 
 // Chunks per ticket of the ordered schedule, by how many bytes a kernel moves per element: one counter serves the
@@ -91,7 +111,7 @@ inline uint32_t span_of(SpanKind k)
 }
 
 // Arguments every ordered kernel starts with.
-#define ORDERED_ARGS(p, kind) (p)->d_tensors, (p)->d_chunks_ordered, (p)->nfull, (uint32_t)(p)->chunks, ccf::span_of(kind)
+#define ORDERED_ARGS(p, kind) (p)->lay().d_tensors, (p)->lay().d_chunks_ordered, (p)->lay().nfull, (uint32_t)(p)->chunks(), ccf::span_of(kind)
 
 
 // Launch entry points, one family per source file.  `mode` = kModeGuard | kModeL2 bits.
@@ -106,5 +126,8 @@ void launch_reduce_half(const cc_plan *p, const StepScalars &s, int32_t *flag, h
 void launch_adam_from_sum(const cc_plan *p, const StepScalars &s, const int32_t *flag, hipStream_t st, int mode, bool sum16);
 int cast_launch(cc_plan *p, const StepScalars &s, const int32_t *flag, hipStream_t st, int guarded);
 int clear_flag(int32_t *flag, hipStream_t st);
+// One fp16-slice tensor, no plan: one workgroup of kSmallBlock per kSmallChunkElems elements, counted on `fs`.
+void launch_fused_adam_flat_f16(const DevTensor &t, int R, unsigned grid, bool resident, const StepScalars &s, FlagScratch *fs,
+                                int32_t *flag, hipStream_t st, int mode);
 
 }  // namespace ccf

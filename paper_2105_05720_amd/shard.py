@@ -19,12 +19,15 @@ from .workloads import aligned_offsets
 class Shard:
     def __init__(self, numels: Sequence[int], weight_decays: Sequence[float], R: int, device="cuda",
                  chunk_elems: int = 0, in_place: bool = False, align_elems: int = 4096, skew_elems: int = 0,
-                 grad_dtype: torch.dtype = torch.float16, schedule: int = cc.CC_SCHEDULE_AUTO, workgroups: int = 0):
+                 grad_dtype: torch.dtype = torch.float16, schedule: int = cc.CC_SCHEDULE_AUTO, workgroups: int = 0,
+                 cache_policy: int = cc.CC_CACHE_AUTO, unfused: Optional[bool] = None):
         """align_elems: tensor starts are multiples of this many elements (>= 8 keeps them 16-byte aligned
         in the fp16 arenas).  The default places every tensor on a chunk boundary (4096 elements = 16 KiB of
         fp32), which measures ~5 % faster than 256-byte alignment: a chunk then covers whole DRAM interleave
         units instead of straddling them.  skew_elems shifts the whole arena start (multiple of 8).
-        schedule / workgroups: passed to cc_plan_set_schedule for both plans (AUTO leaves the library's choice)."""
+        schedule / workgroups: passed to cc_plan_set_schedule for both plans (AUTO leaves the library's choice).
+        cache_policy: passed to cc_plan_set_cache_policy.  unfused: also reserve the unfused pipelines' intermediate
+        buffer (4 bytes per element and plan), which cc_unfused_* need; None reserves it for shards below 32 Mi elements."""
         assert align_elems % 8 == 0 and skew_elems % 8 == 0
         self.numels = list(numels)
         self.wds = list(weight_decays)
@@ -63,6 +66,14 @@ class Shard:
                                                    cc.CC_GRAD_F16 if grad_dtype == torch.float16 else cc.CC_GRAD_F32))
             if schedule != cc.CC_SCHEDULE_AUTO or workgroups:
                 cc.cc_plan_set_schedule(self.plans[-1], schedule, workgroups)
+            if cache_policy != cc.CC_CACHE_AUTO:
+                cc.cc_plan_set_cache_policy(self.plans[-1], cache_policy)
+        if unfused or (unfused is None and total < (32 << 20)):
+            self.reserve_unfused()
+
+    def reserve_unfused(self) -> None:
+        for p in self.plans:
+            cc.cc_plan_reserve_unfused(p)
 
     def _addr(self, arena: torch.Tensor, k: int, itemsize: int) -> int:
         return arena.data_ptr() + (self.skew + self.offsets[k]) * itemsize

@@ -28,7 +28,7 @@ def test_library_exports_every_declared_symbol():
         assert n in cc.EXPORTS, "binding does not type %s" % n
         assert hasattr(cc, n), "binding has no function %s" % n
     assert set(cc.EXPORTS) == set(names)
-    assert cc.cc_version() == 100
+    assert cc.cc_version() == 200
 
 
 def test_struct_layout_matches_header():
@@ -141,6 +141,43 @@ def test_plan_create_rejects_bad_arguments_on_the_host(kw, R, code):
     assert cc.cc_last_error()
 
 
+# Overlap rules (checked on the host before any device call): an output buffer may share memory only with its own
+# in-place input.  numel = 4096: fp32 buffers span 0x4000 bytes, fp16 ones 0x2000.
+@pytest.mark.parametrize("tensors", [
+    [dict(w16_out=0x30000 + 0x1000)],                                   # fp16 copy inside w_out
+    [dict(grad=[0x40000 + 0x100, 0x80000])],                            # a gradient slice inside m_out
+    [dict(v_in=0x30000)],                                               # v_in is w_out (not its own output)
+    [dict(w_in=0x30000, w_out=0x30000, m_in=0x40000 + 16)],             # in place for w, m_in partially over m_out
+    [dict(), dict(w_in=0x101000, m_in=0x110000, v_in=0x120000, w_out=0x50000 + 0x2000, m_out=0x140000, v_out=0x150000,
+                  w16_out=0x160000, grad=[0x170000, 0x180000])],       # tensor 1's w_out inside tensor 0's v_out
+    [dict(), dict(w_in=0x101000, m_in=0x110000, v_in=0x120000, w_out=0x130000, m_out=0x140000, v_out=0x150000,
+                  w16_out=0x160000, grad=[0x60000, 0x180000])],        # tensor 1's gradient is tensor 0's fp16 output
+    [dict(), dict(w_in=0x101000, m_in=0x110000, v_in=0x120000, w_out=0x130000, m_out=0x140000, v_out=0x150000,
+                  w16_out=0x60000 + 0x1ff0, grad=[0x170000, 0x180000])],  # the two fp16 outputs share their last 16 bytes
+])
+def test_plan_create_rejects_overlaps_that_involve_an_output(tensors):
+    with pytest.raises(cc.CcError) as e:
+        cc.cc_plan_create([_tensor(**kw) for kw in tensors], 2)
+    assert e.value.code == cc.CC_ERR_ALIAS
+    assert "overlaps" in cc.cc_last_error()
+
+
+@pytest.mark.parametrize("tensors", [
+    [dict(grad=[0x70000, 0x70000])],                                    # the same slice twice: inputs may overlap inputs
+    [dict(w_in=0x30000, w_out=0x30000, m_in=0x40000, m_out=0x40000, v_in=0x50000, v_out=0x50000)],   # in place
+    [dict(w16_out=0x62000 - 0x2000)],                                   # buffers that touch end to start do not overlap
+    [dict(), dict(numel=0, w_in=0, m_in=0, v_in=0, w_out=0, m_out=0, v_out=0, w16_out=0, grad=[0, 0])],   # empty tensors are not looked at
+])
+def test_plan_create_accepts_the_legal_sharing(tensors):
+    # without a device the call gets past the host checks and then fails in the runtime; with one it succeeds
+    try:
+        plan = cc.cc_plan_create([_tensor(**kw) for kw in tensors], 2)
+    except cc.CcError as e:
+        assert e.code == cc.CC_ERR_HIP, cc.cc_last_error()
+    else:
+        plan.destroy()
+
+
 def test_plan_create_rejects_empty_list_and_bad_chunk():
     with pytest.raises(cc.CcError) as e:
         cc.cc_plan_create([], 2)
@@ -164,6 +201,18 @@ def test_step_calls_reject_null_plan_and_bad_copy_arguments():
     assert lib.cc_plan_schedule(None, None, None) == cc.CC_ERR_NULL
     assert lib.cc_plan_autotune(None, C.byref(hp), 0, 0x1000, None, None, None) == cc.CC_ERR_NULL
     assert "plan is NULL" in cc.cc_last_error()
+    assert lib.cc_plan_set_chunk_elems(None, 0) == cc.CC_ERR_NULL
+    assert lib.cc_plan_layout(None, None, None, None) == cc.CC_ERR_NULL
+    assert lib.cc_plan_set_cache_policy(None, 0) == cc.CC_ERR_NULL
+    assert lib.cc_plan_reserve_unfused(None) == cc.CC_ERR_NULL
+    assert lib.cc_plan_queue_state(None, None, None, None) == cc.CC_ERR_NULL
+    assert lib.cc_pattern_probe(None, 4, 0, cc.CC_CACHE_STREAMING, 0x1000, None) == cc.CC_ERR_NULL
+    t = cc._c_tensor(_tensor())
+    assert lib.cc_pattern_probe(C.byref(t), 5, 0, cc.CC_CACHE_STREAMING, 0x1000, None) == cc.CC_ERR_ARG
+    assert lib.cc_pattern_probe(C.byref(t), 4, 7, cc.CC_CACHE_STREAMING, 0x1000, None) == cc.CC_ERR_ARG
+    t.numel = 1000
+    assert lib.cc_pattern_probe(C.byref(t), 4, 1, cc.CC_CACHE_RESIDENT, 0x1000, None) == cc.CC_ERR_ARG
+    assert "multiple of 1024" in cc.cc_last_error()
 
 
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):

@@ -1,0 +1,129 @@
+"""What a plan may vary without changing results: chunk size, cache policy; and what the unfused pipelines need first.
+
+Adam is independent per element, so every chunk size and both cache policies must give the same bits.  LAMB adds its
+per-chunk partial sums in double in a fixed order per chunk size; another chunk size groups them differently, so its
+results move within rounding of the norms (checked against the oracle at the parity bar) while the cache policy leaves
+the bits alone."""
+import pytest
+import torch
+
+import oracle
+from paper_2105_05720_amd import binding as cc
+from paper_2105_05720_amd.shard import Shard
+from parity import OracleState, hyper_pair, run_steps, seeded_grads, seeded_state
+
+pytestmark = pytest.mark.gpu
+
+LIST = [16384 * 2 + 4097, 0, 1, 4096 * 3, 1024 * 9 + 1023, 8192, 777, 16384]
+
+
+def wds_for(numels, wd=0.01):
+    return [wd if (i % 3) else 0.0 for i in range(len(numels))]
+
+
+def bits_of(sh):
+    c = sh.cur
+    return [sh.w[c].view(torch.int32).clone(), sh.m[c].view(torch.int32).clone(), sh.v[c].view(torch.int32).clone(),
+            sh.w16[c].view(torch.int16).clone()]
+
+
+def run_shape(fn, ofn, chunk, policy, R=4, grad_dtype=torch.float16, steps=2, numels=LIST):
+    sh = Shard(numels, wds_for(numels), R, align_elems=8, grad_dtype=grad_dtype)
+    for p in sh.plans:
+        cc.cc_plan_set_chunk_elems(p, chunk)
+        cc.cc_plan_set_cache_policy(p, policy)
+        assert cc.cc_plan_layout(p)[0] == chunk
+        want = cc.CC_CACHE_RESIDENT if (policy == cc.CC_CACHE_RESIDENT and chunk < 4096) else cc.CC_CACHE_STREAMING
+        assert cc.cc_plan_layout(p)[2] == want
+    seeded_state(sh, 5)
+    ost = OracleState(sh, range(len(numels)))
+    run_steps(sh, ost, fn, ofn, [hyper_pair(step=t) for t in range(1, steps + 1)], "chunk %d policy %d" % (chunk, policy),
+              lambda i: seeded_grads(sh, 500 + i, 1e-2), expect_flags=[0] * steps)
+    out = bits_of(sh)
+    sh.destroy()
+    return out
+
+
+@pytest.mark.parametrize("fn,ofn", [(cc.cc_fused_adam_step, oracle.adam_step), (cc.cc_unfused_adam_step, oracle.adam_step)])
+def test_adam_bits_do_not_depend_on_chunk_size_or_cache_policy(fn, ofn):
+    ref = run_shape(fn, ofn, 1024, cc.CC_CACHE_STREAMING)
+    for chunk, policy in ((1024, cc.CC_CACHE_RESIDENT), (4096, cc.CC_CACHE_STREAMING), (16384, cc.CC_CACHE_STREAMING),
+                          (4096, cc.CC_CACHE_RESIDENT)):
+        got = run_shape(fn, ofn, chunk, policy)
+        assert all(torch.equal(a, b) for a, b in zip(ref, got)), "chunk %d policy %d changes Adam's bits" % (chunk, policy)
+
+
+@pytest.mark.parametrize("fn", [cc.cc_fused_lamb_step, cc.cc_unfused_lamb_step])
+def test_lamb_every_chunk_size_and_policy_against_oracle(fn):
+    per_chunk = {}
+    for chunk, policy in ((1024, cc.CC_CACHE_STREAMING), (1024, cc.CC_CACHE_RESIDENT), (4096, cc.CC_CACHE_STREAMING),
+                          (16384, cc.CC_CACHE_STREAMING)):
+        got = run_shape(fn, oracle.lamb_step, chunk, policy)
+        if chunk in per_chunk:          # same chunk size, other cache policy: the same bits
+            assert all(torch.equal(a, b) for a, b in zip(per_chunk[chunk], got))
+        per_chunk[chunk] = got
+
+
+@pytest.mark.parametrize("R", [1, 8, 16])
+def test_resident_policy_every_kind_of_R_and_fp32_slices(R):
+    for gd in (torch.float16, torch.float32):
+        a = run_shape(cc.cc_fused_adam_step, oracle.adam_step, 1024, cc.CC_CACHE_RESIDENT, R=R, grad_dtype=gd, steps=1)
+        b = run_shape(cc.cc_fused_adam_step, oracle.adam_step, 1024, cc.CC_CACHE_STREAMING, R=R, grad_dtype=gd, steps=1)
+        assert all(torch.equal(x, y) for x, y in zip(a, b))
+
+
+def test_single_tensor_plan_resident_and_streaming():
+    """One tensor: the table-free kernel, both policies, against the oracle (2^17 + a ragged end)."""
+    for policy in (cc.CC_CACHE_RESIDENT, cc.CC_CACHE_STREAMING):
+        run_shape(cc.cc_fused_adam_step, oracle.adam_step, 1024, policy, numels=[(1 << 17) + 5], steps=2)
+
+
+def test_auto_policy_and_layout_rules():
+    small = Shard([1 << 20], [0.0], 4, align_elems=8)
+    assert cc.cc_plan_layout(small.plans[0]) == (1024, 128, cc.CC_CACHE_RESIDENT)      # 35.7 MB of buffers: stays on chip
+    cc.cc_plan_set_cache_policy(small.plans[0], cc.CC_CACHE_STREAMING)
+    assert cc.cc_plan_layout(small.plans[0])[2] == cc.CC_CACHE_STREAMING
+    cc.cc_plan_set_cache_policy(small.plans[0], cc.CC_CACHE_AUTO)
+    cc.cc_plan_set_chunk_elems(small.plans[0], 4096)
+    assert cc.cc_plan_layout(small.plans[0]) == (4096, 512, cc.CC_CACHE_STREAMING)     # resident exists for 128-thread workgroups only
+    with pytest.raises(cc.CcError) as e:
+        cc.cc_plan_set_chunk_elems(small.plans[0], 2048)
+    assert e.value.code == cc.CC_ERR_ARG
+    with pytest.raises(cc.CcError):
+        cc.cc_plan_set_cache_policy(small.plans[0], 9)
+    cc.cc_plan_set_chunk_elems(small.plans[0], 0)
+    assert cc.cc_plan_layout(small.plans[0])[0] == 1024
+    small.destroy()
+    fixed = Shard([1 << 16], [0.0], 2, chunk_elems=2048, align_elems=8)                 # a caller's own chunk size: that one only
+    assert cc.cc_plan_layout(fixed.plans[0])[:2] == (2048, 128)
+    with pytest.raises(cc.CcError):
+        cc.cc_plan_set_chunk_elems(fixed.plans[0], 4096)
+    fixed.destroy()
+
+
+def test_unfused_steps_need_the_reserved_buffer_and_never_allocate():
+    sh = Shard([5000, 3], [0.01, 0.0], 2, align_elems=8, unfused=False)
+    seeded_state(sh, 3)
+    seeded_grads(sh, 30, 1e-2)
+    before = bits_of(sh)
+    for fn in (cc.cc_unfused_adam_step, cc.cc_unfused_lamb_step):
+        with pytest.raises(cc.CcError) as e:
+            sh.run(fn, cc.Hyper())
+        assert e.value.code == cc.CC_ERR_ARG and "cc_plan_reserve_unfused" in cc.cc_last_error()
+    torch.cuda.synchronize()
+    assert all(torch.equal(a, b) for a, b in zip(before, bits_of(sh)))
+    sh.reserve_unfused()
+    sh.reserve_unfused()                                   # a second call does nothing
+    # the very first unfused call can be captured into a graph: nothing is allocated or copied by a step call
+    ref = Shard([5000, 3], [0.01, 0.0], 2, align_elems=8, unfused=True)
+    seeded_state(ref, 3)
+    seeded_grads(ref, 30, 1e-2)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        sh.run(cc.cc_unfused_adam_step, cc.Hyper())
+    g.replay()
+    ref.run(cc.cc_unfused_adam_step, cc.Hyper())
+    torch.cuda.synchronize()
+    sh.commit(); ref.commit()
+    assert all(torch.equal(a, b) for a, b in zip(bits_of(sh), bits_of(ref)))
+    sh.destroy(); ref.destroy()

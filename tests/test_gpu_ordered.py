@@ -140,8 +140,13 @@ def test_ordered_queue_is_clean_between_launches_and_kernels():
         seeded_state(sh, 11)
         seeded_grads(sh, 1100, 1e-2)
     ghp, _ = hyper_pair(step=1)
-    for fn in (cc.cc_fused_lamb_step, cc.cc_unfused_adam_step, cc.cc_unfused_lamb_step, cc.cc_fused_adam_step) * 3:
+    for i, fn in enumerate((cc.cc_fused_lamb_step, cc.cc_unfused_adam_step, cc.cc_unfused_lamb_step, cc.cc_fused_adam_step) * 3):
         a.run(fn, ghp)          # writes the uncommitted copy only
+        if i % 2 == 0:          # the ticket counter and the finished-workgroup word are zero after every step
+            assert cc.cc_plan_queue_state(a.plans[a.cur]) == (0, 0)
+    for _ in range(200):        # many launches back to back, then look once more
+        a.run(cc.cc_fused_adam_step, ghp)
+    assert cc.cc_plan_queue_state(a.plans[a.cur]) == (0, 0)
     a.run(cc.cc_fused_adam_step, ghp)
     b.run(cc.cc_fused_adam_step, ghp)
     torch.cuda.synchronize()
@@ -169,6 +174,40 @@ def test_schedule_selection_and_errors():
     cc.cc_plan_set_schedule(sh.plans[0], ORDERED, 64)
     assert cc.cc_plan_schedule(sh.plans[0]) == (ORDERED, 2)                       # never more than pairs of chunks
     sh.destroy()
+
+
+@pytest.mark.parametrize("optimizer", [0, 1])
+def test_autotune_over_chunk_sizes_gives_the_oracle_result(optimizer):
+    """A plan prepared for every chunk size: the tuner may land on any chunk size, schedule and cache policy; whatever it
+    keeps, the steps that follow must agree with the oracle, and the trial steps must leave the committed copy alone."""
+    numels = [4096 * 300 + 17, 4096 * 200, 5, 0, 16384 * 3 + 1]
+    fn, ofn = (cc.cc_fused_adam_step, oracle.adam_step) if optimizer == 0 else (cc.cc_fused_lamb_step, oracle.lamb_step)
+    tuned = Shard(numels, wds_for(numels), 4, align_elems=8)
+    seeded_state(tuned, 19)
+    seeded_grads(tuned, 1900, 1e-2)
+    ghp, _ = hyper_pair(step=1)
+    committed = [x.clone() for x in (tuned.w[0], tuned.m[0], tuned.v[0], tuned.w16[0])]
+    # the trial steps of a plan write that plan's out buffers: tune the plan that reads the committed copy, then give the
+    # other one (which writes the committed copy) the same shape by hand
+    best_ms, per_chunk_ms = cc.cc_plan_autotune(tuned.plans[0], ghp, tuned.flag, optimizer)
+    assert 0.0 < best_ms <= per_chunk_ms * 1.0001
+    chunk, block, policy = cc.cc_plan_layout(tuned.plans[0])
+    assert chunk in (1024, 4096, 16384) and block == (128 if chunk == 1024 else 512)
+    assert policy in (cc.CC_CACHE_STREAMING, cc.CC_CACHE_RESIDENT)
+    sched, wgs = cc.cc_plan_schedule(tuned.plans[0])
+    assert sched in (cc.CC_SCHEDULE_PER_CHUNK, cc.CC_SCHEDULE_ORDERED) and wgs >= 1
+    assert sched == cc.CC_SCHEDULE_PER_CHUNK or chunk == 4096
+    cc.cc_plan_set_schedule(tuned.plans[1], cc.CC_SCHEDULE_PER_CHUNK, 0)
+    cc.cc_plan_set_chunk_elems(tuned.plans[1], chunk)
+    cc.cc_plan_set_schedule(tuned.plans[1], sched, wgs if sched == cc.CC_SCHEDULE_ORDERED else 0)
+    cc.cc_plan_set_cache_policy(tuned.plans[1], policy)
+    assert cc.cc_plan_layout(tuned.plans[1]) == (chunk, block, policy)
+    for a, b in zip(committed, (tuned.w[0], tuned.m[0], tuned.v[0], tuned.w16[0])):
+        assert torch.equal(a, b)
+    ost = OracleState(tuned, range(len(numels)))
+    run_steps(tuned, ost, fn, ofn, [hyper_pair(step=t) for t in (1, 2, 3)], "tuned plan", lambda i: seeded_grads(tuned, 1900 + i, 1e-2),
+              expect_flags=[0, 0, 0])
+    tuned.destroy()
 
 
 @pytest.mark.parametrize("optimizer", [0, 1])
