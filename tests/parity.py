@@ -139,3 +139,110 @@ def seeded_grads(shard: Shard, seed: int, std: float):
         tmp = torch.empty(arena.numel(), dtype=torch.float32, device=shard.device)
         tmp.normal_(0.0, std, generator=g)
         arena.copy_(tmp)
+
+
+# ---- full-size comparison: the oracle over EVERY element, streamed in batches; the comparison itself runs on the device ----
+
+def device_state_ratio(got: torch.Tensor, want_np: np.ndarray):
+    """state_error() of util.py evaluated with torch on the device (a library routine as test plumbing, float64):
+    (worst |x-y| / (REL_TOL max(|y|, rms(y))), worst pure relative error)."""
+    if got.numel() == 0:
+        return 0.0, 0.0
+    y = torch.from_numpy(want_np).to(got.device).double()
+    x = got.double()
+    fx, fy = torch.isfinite(x), torch.isfinite(y)
+    if not torch.equal(fx, fy):
+        return float("inf"), float("inf")
+    x, y = x[fy], y[fy]
+    if x.numel() == 0:
+        return 0.0, 0.0
+    rms = torch.sqrt(torch.mean(y * y))
+    diff = (x - y).abs()
+    floor = torch.maximum(y.abs(), rms)
+    ratio = diff / (REL_TOL * torch.where(floor > 0, floor, torch.ones_like(floor)))
+    ratio = torch.where((floor == 0) & (diff == 0), torch.zeros_like(ratio), ratio)
+    rel = torch.where(y != 0, diff / y.abs(), torch.where(diff == 0, torch.zeros_like(diff), torch.full_like(diff, float("inf"))))
+    return float(ratio.max().item()), float(rel.max().item())
+
+
+def device_half_ulp_max(got_half: torch.Tensor, want_bits_np: np.ndarray) -> int:
+    """Largest distance on the ordered fp16 line between two sets of bit patterns (two non-finite values are equal)."""
+    if got_half.numel() == 0:
+        return 0
+    a = got_half.view(torch.int16).to(torch.int64) & 0xFFFF
+    b = torch.from_numpy(want_bits_np.view(np.int16)).to(got_half.device).to(torch.int64) & 0xFFFF
+
+    def key(x):
+        mag = x & 0x7FFF
+        return torch.where((x & 0x8000) != 0, -mag, mag)
+    d = (key(a) - key(b)).abs()
+    both = ((a & 0x7C00) == 0x7C00) & ((b & 0x7C00) == 0x7C00)
+    return int(torch.where(both, torch.zeros_like(d), d).max().item())
+
+
+class FullOracle:
+    """The oracle's own fp32 state of EVERY tensor of a shard on the host, advanced only by the oracle.  A step pulls the
+    gradients from the device batch by batch (they are the seeded inputs both sides read), runs the oracle on each batch
+    and keeps the new state aside until the flag of the whole step is known (whole-step skip spans all tensors)."""
+
+    def __init__(self, shard: Shard, batch_elems: int = 160_000_000, piece_elems: int = 8_000_000):
+        self.T = len(shard.numels)
+        self.w = [to_np_f32(shard.w_of(k)) for k in range(self.T)]
+        self.m = [to_np_f32(shard.m_of(k)) for k in range(self.T)]
+        self.v = [to_np_f32(shard.v_of(k)) for k in range(self.T)]
+        self.w16 = [to_np_bits(shard.w16_of(k)) for k in range(self.T)]
+        self.norms = [None] * self.T
+        self.piece_elems = piece_elems
+        self.batches, cur, size = [], [], 0
+        for k, n in enumerate(shard.numels):
+            if cur and size + n > batch_elems:
+                self.batches.append(cur)
+                cur, size = [], 0
+            cur.append(k)
+            size += n
+        if cur:
+            self.batches.append(cur)
+        self.elements = sum(shard.numels)
+
+    def step(self, shard: Shard, ohp, optimizer: str) -> int:
+        """One oracle step over all tensors.  Returns the flag; on a skipped step the state stays as it was."""
+        new = {}
+        flag = 0
+        for batch in self.batches:
+            grads = {k: [grad_to_np(shard, shard.grad_of(r, k)) for r in range(shard.R)] for k in batch}
+            ots, owner = [], []
+            for k in batch:
+                n = self.w[k].size
+                # Adam is independent per element: a huge tensor is handed over in pieces so that all host threads work
+                # on it; a LAMB tensor is one trust-ratio unit and stays whole
+                step_n = self.piece_elems if (optimizer == "adam" and n > self.piece_elems) else max(n, 1)
+                for a in range(0, max(n, 1), step_n):
+                    b = min(n, a + step_n)
+                    ots.append(oracle.OracleTensor(w=self.w[k][a:b], m=self.m[k][a:b], v=self.v[k][a:b],
+                                                   grads=[g[a:b] for g in grads[k]], weight_decay=shard.wds[k]))
+                    owner.append(k)
+            f = (oracle.adam_step if optimizer == "adam" else oracle.lamb_step)(ots, ohp, threads=THREADS)
+            flag |= f
+            for k in batch:
+                mine = [t for t, o in zip(ots, owner) if o == k]
+                cat = (lambda xs: xs[0] if len(xs) == 1 else np.concatenate(xs))
+                new[k] = (cat([t.w_out for t in mine]), cat([t.m_out for t in mine]), cat([t.v_out for t in mine]),
+                          cat([t.w16_out for t in mine]), mine[0].norms if optimizer == "lamb" else None)
+        if flag and ohp.skip_mode == 0:
+            return flag                         # every tensor keeps its state, also those of batches without an inf/NaN
+        for k, (w, m, v, h, norms) in new.items():
+            self.w[k], self.m[k], self.v[k], self.w16[k], self.norms[k] = w, m, v, h, norms
+        return flag
+
+    def compare(self, shard: Shard, label: str):
+        """Every element of the committed device state against the oracle's, to the parity bar.  Returns the worst
+        ratio to the bound over all tensors."""
+        worst = 0.0
+        for k in range(self.T):
+            for name, got, want in (("w", shard.w_of(k), self.w[k]), ("m", shard.m_of(k), self.m[k]), ("v", shard.v_of(k), self.v[k])):
+                ratio, rel = device_state_ratio(got, want)
+                worst = max(worst, ratio)
+                assert ratio <= 1.0, "%s: tensor %d %s off by %.3g x the %.0e bound (max rel %.3g)" % (label, k, name, ratio, REL_TOL, rel)
+            d = device_half_ulp_max(shard.w16_of(k), self.w16[k])
+            assert d <= 1, "%s: tensor %d fp16 weights differ by %d ulp" % (label, k, d)
+        return worst
