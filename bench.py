@@ -3,11 +3,14 @@
 
 A step is one fused reduce+Adam pass (chunk lookup, R-way fp16 reduce, unscale and overflow test, moments,
 weight update, fp16 emission) over the BERT-Large parameter list with R = 8 gradient slices (configuration 2),
-inputs resident in HBM.  The same run also times, with the same method, the fused LAMB step on that list
-(configuration 3), the unfused reduce / optimizer / cast pipelines, a plain copy kernel (the practical HBM
-ceiling) and the CPU oracle on a bounded sample.  One JSON line is printed.
+inputs resident in HBM.  The same run also times, with the same method, the four other configurations (the fused
+LAMB step on that list, the GPT-2 1.5B list with Adam, the 1/8 shard of an 8.3B transformer with LAMB, and the
+2^20-element tensor with eager launches, graph replay and evicted caches), the unfused reduce / optimizer / cast
+pipelines, a plain copy kernel (the practical HBM ceiling) and the CPU oracle on a bounded sample.  One JSON line is
+printed.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--chunk-elems N] [--no-extras]
+    python bench.py --mode sweep|rsweep|epilogue|small   (measurement programs behind profiles/*.md, see bench_sweeps.py)
 """
 from __future__ import annotations
 
@@ -25,27 +28,118 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 
 # HBM bytes per launch of the headline kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by what
 # the same counter reads for the plain copy kernel: default chunk size and schedule, fp16 slices, scattered list only.
-MEASURED_TRAFFIC_BYTES = {2: 9.4495e9 + 4.7096e9, 3: 1.3500e10 + 4.7133e9,        # profiles/fused_adam_config2.md, fused_lamb_config3.md
-                          4: 4.3673e10 + 2.1818e10, 5: 4.1659e10 + 1.4574e10}     # profiles/fused_adam_config4.md, fused_lamb_config5.md
+# These are constants copied from the kept profiles, not measured by this run.
+MEASURED_TRAFFIC = {2: (9.4495e9 + 4.7096e9, "profiles/fused_adam_config2.md"),
+                    3: (1.3500e10 + 4.7133e9, "profiles/fused_lamb_config3.md"),
+                    4: (4.3673e10 + 2.1818e10, "profiles/fused_adam_config4.md"),
+                    5: (4.1659e10 + 1.4574e10, "profiles/fused_lamb_config5.md")}
+
+WORKLOAD_NAMES = {1: "one flat tensor", 2: "BERT-Large parameter list", 3: "BERT-Large parameter list",
+                  4: "GPT-2 1.5B parameter list", 5: "1/8 shard of an 8.3B transformer"}
 
 
-GRAD_BYTES = 2                 # bytes per gradient element (set to 4 by --grad-dtype f32)
+def adam_bytes_per_param(R, gb=2):   # read gb R (gradient slices) + 12 (w, m, v); write 12 (w, m, v) + 2 (fp16 w)
+    return gb * R + 26
 
 
-def adam_bytes_per_param(R):   # read 2R (fp16 grads) + 12 (w, m, v); write 12 (w, m, v) + 2 (fp16 w)
-    return GRAD_BYTES * R + 26
+def lamb_bytes_per_param(R, gb=2):   # phase 1: read gb R + 12, write 8; phase 2: read 12, write 6
+    return gb * R + 38
 
 
-def lamb_bytes_per_param(R):   # phase 1: read 2R + 12, write 8; phase 2: read 12, write 6
-    return GRAD_BYTES * R + 38
+def unfused_adam_bytes_per_param(R, gb=2):   # reduce: gb R + 4; optimizer: 16 + 12; cast: 4 + 2
+    return gb * R + 38
 
 
-def unfused_adam_bytes_per_param(R):   # reduce: 2R + 4; optimizer: 16 + 12; cast: 4 + 2
-    return GRAD_BYTES * R + 38
+def unfused_lamb_bytes_per_param(R, gb=2):   # reduce gb R + 4; phase 1: 16 + 8; phase 2: 12 + 4; cast 4 + 2
+    return gb * R + 50
 
 
-def unfused_lamb_bytes_per_param(R):   # reduce 2R + 4; phase 1: 16 + 8; phase 2: 12 + 4; cast 4 + 2
-    return GRAD_BYTES * R + 50
+class Timer:
+    """Times consecutive optimizer steps of one shard with HIP events on the launch stream (torch's current stream,
+    which is also the stream the binding launches on)."""
+
+    def __init__(self, torch, cc, shard, cfg, skip_mode=0):
+        self.torch, self.cc, self.shard, self.cfg, self.skip_mode = torch, cc, shard, cfg, skip_mode
+        self.t = 1
+
+    def hyper(self, t):
+        c = self.cfg
+        return self.cc.Hyper(lr=c.lr, beta1=c.beta1, beta2=c.beta2, eps=c.eps, loss_scale=c.loss_scale, step=t,
+                             skip_mode=self.skip_mode)
+
+    def run(self, fn, steps, warmup, graph=False):
+        """warmup + steps consecutive steps, each reading the copy the previous one wrote; events bracket exactly
+        `steps` of them.  graph: the timed steps are replays of a captured graph of 20 steps (an even number, so that the
+        ping-pong state is back where it started; the step count t is baked into the recording).  Returns ms per step."""
+        torch, shard = self.torch, self.shard
+        for _ in range(warmup):
+            shard.run(fn, self.hyper(self.t))
+            shard.commit()
+            self.t += 1
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        if graph:
+            per = 20
+            assert steps % per == 0, "graph replay needs a multiple of 20 steps"
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                for i in range(per):
+                    shard.run(fn, self.hyper(self.t + i))
+                    shard.commit()
+            for _ in range(max(1, warmup // per)):
+                g.replay()
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(steps // per):
+                g.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            self.t += per
+        else:
+            e0.record()
+            for _ in range(steps):
+                shard.run(fn, self.hyper(self.t))
+                shard.commit()
+                self.t += 1
+            e1.record()
+            torch.cuda.synchronize()
+        assert int(shard.flag.item()) == 0, "overflow flag set during the timed run"
+        return e0.elapsed_time(e1) / steps
+
+    def cold(self, fn, evict, reps=30):
+        """Median ms of one step whose caches were evicted first (evict() enqueues a copy far larger than the 256 MB
+        Infinity Cache); the event pair brackets the step alone."""
+        torch, shard = self.torch, self.shard
+        times = []
+        for _ in range(reps):
+            evict()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            shard.run(fn, self.hyper(self.t))
+            b.record()
+            shard.commit()
+            self.t += 1
+            torch.cuda.synchronize()
+            times.append(a.elapsed_time(b))
+        times.sort()
+        return times[len(times) // 2]
+
+
+def describe(cc, shard, R, optimizer, gf32):
+    sched, wgs = cc.cc_plan_schedule(shard.plans[0])
+    chunk, block, policy = cc.cc_plan_layout(shard.plans[0])
+    _, chunks, table_bytes = cc.cc_plan_info(shard.plans[0])
+    ordered = sched == cc.CC_SCHEDULE_ORDERED
+    one = len([n for n in shard.numels if n]) == 1
+    if optimizer == "adam":
+        kernel = "fused_adam%s_kernel<R=%d, %d threads>" % ("_ordered" if ordered else ("_flat" if one else ""), R, block)
+    else:
+        kernel = "lamb_phase1%s_kernel<R=%d, %d threads> + lamb_norms_kernel + lamb_phase2%s_kernel" % (
+            ("_ordered", R, block, "_ordered") if ordered else ("", R, block, ""))
+    return {"chunk_elems": chunk, "chunks": chunks, "table_bytes": table_bytes, "kernel": kernel,
+            "schedule": ("ordered: %d persistent workgroups take the chunks in table order" % wgs) if ordered
+            else "one workgroup of %d threads per chunk" % block,
+            "cache_policy": "plain accesses (cache-resident shard)" if policy == cc.CC_CACHE_RESIDENT else "non-temporal accesses"}
 
 
 def main() -> int:
@@ -53,6 +147,8 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--mode", choices=("step", "sweep", "rsweep", "epilogue", "small"), default="step",
+                    help="step: the benchmark line (default); the others are the measurement programs of bench_sweeps.py")
     ap.add_argument("--config", type=int, default=2, help="workload configuration 1..5 (default 2, the metric's)")
     ap.add_argument("--chunk-elems", type=int, default=0)
     ap.add_argument("--in-place", action="store_true", help="in-place state with the per-element guard (skip_mode 1)")
@@ -62,11 +158,12 @@ def main() -> int:
     ap.add_argument("--schedule", choices=("auto", "per-chunk", "ordered", "tuned"), default="auto",
                     help="how the kernels are laid over the device (cc_plan_set_schedule); auto = the library's size rule, "
                          "tuned = cc_plan_autotune measures the candidates on this workload first")
+    ap.add_argument("--cache", choices=("auto", "streaming", "resident"), default="auto", help="cc_plan_set_cache_policy")
     ap.add_argument("--workgroups", type=int, default=0, help="workgroups of the ordered schedule (0 = one per compute unit)")
     ap.add_argument("--no-extras", action="store_true", help="only the headline step (for profiling runs)")
     ap.add_argument("--copy-only", action="store_true", help="run only the plain copy kernel (2 GiB, 20 launches): counter calibration")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
-    args = ap.parse_args()
+    args, rest = ap.parse_known_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU's shard only (no collectives, no sharding across GPUs); "
@@ -85,6 +182,11 @@ def main() -> int:
     cc.load()                                            # raises if libccfused.so is missing
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
+    if args.mode != "step":
+        import bench_sweeps
+        return bench_sweeps.main(args.mode, rest)
+    if rest:
+        ap.error("unknown arguments: %s" % " ".join(rest))
     if args.copy_only:
         nbytes = 2 << 30
         src = torch.empty(nbytes, dtype=torch.uint8, device=dev).fill_(1)
@@ -94,85 +196,54 @@ def main() -> int:
         torch.cuda.synchronize()
         print(json.dumps({"copy_only": True, "bytes_read_per_launch": nbytes, "bytes_written_per_launch": nbytes, "launches": 20}))
         return 0
-    cfg = W.config(args.config)
-    if args.flat:
-        import dataclasses
-        cfg = dataclasses.replace(cfg, params=(W.ParamSpec("flat", cfg.numel, "matrix"),))
-    R, N = cfg.R, cfg.numel
-    K, Wm = args.steps, args.warmup
 
-    global GRAD_BYTES
-    GRAD_BYTES = 2 if args.grad_dtype == "f16" else 4
-    shard = Shard([s.numel for s in cfg.params], [cfg.wd_of(s) for s in cfg.params], R, device=dev,
-                  chunk_elems=args.chunk_elems, in_place=args.in_place,
-                  grad_dtype=torch.float16 if args.grad_dtype == "f16" else torch.float32,
-                  schedule={"auto": cc.CC_SCHEDULE_AUTO, "per-chunk": cc.CC_SCHEDULE_PER_CHUNK, "ordered": cc.CC_SCHEDULE_ORDERED,
-                            "tuned": cc.CC_SCHEDULE_AUTO}[args.schedule],
-                  workgroups=args.workgroups)
-    W.fill_state(shard, cfg)
-    W.fill_grads(shard, cfg, 1)
-    torch.cuda.synchronize()
+    gb = 2 if args.grad_dtype == "f16" else 4
+    K, Wm = args.steps, args.warmup
+    sched_arg = {"auto": cc.CC_SCHEDULE_AUTO, "per-chunk": cc.CC_SCHEDULE_PER_CHUNK, "ordered": cc.CC_SCHEDULE_ORDERED,
+                 "tuned": cc.CC_SCHEDULE_AUTO}[args.schedule]
+    cache_arg = {"auto": cc.CC_CACHE_AUTO, "streaming": cc.CC_CACHE_STREAMING, "resident": cc.CC_CACHE_RESIDENT}[args.cache]
+    default_options = (args.chunk_elems == 0 and not args.in_place and not args.flat and args.grad_dtype == "f16"
+                       and args.schedule == "auto" and args.workgroups == 0 and args.cache == "auto")
+
+    def make(index, options=True, unfused=False):
+        """(config, shard with state and the first call's gradients in HBM)"""
+        cfg = W.config(index)
+        if options and args.flat:
+            import dataclasses
+            cfg = dataclasses.replace(cfg, params=(W.ParamSpec("flat", cfg.numel, "matrix"),))
+        kw = dict(chunk_elems=args.chunk_elems, in_place=args.in_place, schedule=sched_arg, workgroups=args.workgroups,
+                  cache_policy=cache_arg,
+                  grad_dtype=torch.float16 if args.grad_dtype == "f16" else torch.float32) if options else {}
+        shard = Shard([s.numel for s in cfg.params], [cfg.wd_of(s) for s in cfg.params], cfg.R, device=dev, unfused=unfused, **kw)
+        W.fill_state(shard, cfg)
+        W.fill_grads(shard, cfg, 1)
+        torch.cuda.synchronize()
+        return cfg, shard
+
+    def rate(ms, bytes_pp, N):
+        gbs = bytes_pp * N / (ms * 1e-3) / 1e9
+        return {"ms_per_step": round(ms, 5), "GB/s": round(gbs, 1), "frac": round(gbs / HBM_PEAK_GBS, 4),
+                "params_per_sec": round(N / (ms * 1e-3), 1), "algorithmic_bytes_per_param": bytes_pp}
+
+    cfg, shard = make(args.config, unfused=not args.no_extras)
+    R, N = cfg.R, cfg.numel
     tuned = None
     if args.schedule == "tuned":
         assert not args.in_place, "--schedule tuned needs out-of-place state"
         hp1 = cc.Hyper(lr=cfg.lr, beta1=cfg.beta1, beta2=cfg.beta2, eps=cfg.eps, loss_scale=cfg.loss_scale, step=1)
         tuned = [cc.cc_plan_autotune(p, hp1, shard.flag, 0 if cfg.optimizer == "adam" else 1) for p in shard.plans]
-    sched, wgs = cc.cc_plan_schedule(shard.plans[0])
-    ordered = sched == cc.CC_SCHEDULE_ORDERED
-    _, chunks, table_bytes = cc.cc_plan_info(shard.plans[0])
-    skip_mode = 1 if args.in_place else 0
-
-    def hyper(t):
-        return cc.Hyper(lr=cfg.lr, beta1=cfg.beta1, beta2=cfg.beta2, eps=cfg.eps, loss_scale=cfg.loss_scale, step=t,
-                        skip_mode=skip_mode)
-
-    def timed(step_fn, steps, warmup, t0=1):
-        """warmup + steps consecutive optimizer steps, each reading the copy the previous one wrote; HIP events
-        on the launch stream bracket exactly `steps` of them.  Returns (ms per step, flag seen at the end)."""
-        t = t0
-        for _ in range(warmup):
-            shard.run(step_fn, hyper(t))
-            shard.commit()
-            t += 1
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        if args.graph:
-            # launch-bound sizes: the same calls, recorded once (an even number of steps, so that the ping-pong
-            # state is back where it started) and replayed; the step count t is baked into the recording
-            per = 20
-            assert steps % per == 0, "--graph needs --steps to be a multiple of 20"
-            g = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g):
-                for i in range(per):
-                    shard.run(step_fn, hyper(t + i))
-                    shard.commit()
-            g.replay()
-            torch.cuda.synchronize()
-            e0.record()
-            for _ in range(steps // per):
-                g.replay()
-            e1.record()
-            torch.cuda.synchronize()
-            return e0.elapsed_time(e1) / steps, int(shard.flag.item()), t + per
-        e0.record()
-        for _ in range(steps):
-            shard.run(step_fn, hyper(t))
-            shard.commit()
-            t += 1
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / steps, int(shard.flag.item()), t
-
+    timer = Timer(torch, cc, shard, cfg, skip_mode=1 if args.in_place else 0)
     headline_fn = cc.cc_fused_adam_step if cfg.optimizer == "adam" else cc.cc_fused_lamb_step
-    bpp = adam_bytes_per_param(R) if cfg.optimizer == "adam" else lamb_bytes_per_param(R)
+    bpp = adam_bytes_per_param(R, gb) if cfg.optimizer == "adam" else lamb_bytes_per_param(R, gb)
 
     # ---- the K timed steps of the headline path -------------------------------------------------------------
     torch.cuda.synchronize()
     wall0 = time.perf_counter()
-    ms, flag, t_next = timed(headline_fn, K, Wm)
+    ms = timer.run(headline_fn, K, Wm, graph=args.graph)
     wall = time.perf_counter() - wall0
-    assert flag == 0, "overflow flag set during the timed run"
     gbs = bpp * N / (ms * 1e-3) / 1e9
+    what = describe(cc, shard, R, cfg.optimizer, gb == 4)
+    traffic = MEASURED_TRAFFIC.get(cfg.index) if default_options else None
     out = {
         "metric": "fused reduce+optimizer HBM GB/s (% of MI355X peak) and params updated/sec",
         "value": round(gbs, 1), "unit": "GB/s",
@@ -183,82 +254,63 @@ def main() -> int:
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "config %d: fused %s, %s, T=%d tensors, N=%d fp32 params, R=%d fp16 gradient slices, "
                                "%s state" % (cfg.index, cfg.optimizer,
-                                             "the same N as ONE contiguous tensor" if args.flat else
-                                             {1: "one flat tensor", 2: "BERT-Large parameter list", 3: "BERT-Large parameter list",
-                                              4: "GPT-2 1.5B parameter list", 5: "1/8 shard of an 8.3B transformer"}[cfg.index],
+                                             "the same N as ONE contiguous tensor" if args.flat else WORKLOAD_NAMES[cfg.index],
                                              len(cfg.params), N, R, "in-place" if args.in_place else "out-of-place (ping-pong)") + (
                                                  " [fp32 gradient slices]" if args.grad_dtype == "f32" else ""),
-                   "chunk_elems": (N + chunks - 1) // chunks if cfg.index == 1 and chunks else (args.chunk_elems or cc.cc_default_chunk_elems()),
-                   "chunks": chunks, "launch": "hip graph replay" if args.graph else "eager",
-                   "schedule": ("ordered: %d persistent workgroups take the chunks in table order" % wgs) if ordered
-                   else "one workgroup per chunk",
+                   "chunk_elems": what["chunk_elems"], "chunks": what["chunks"],
+                   "launch": "hip graph replay" if args.graph else "eager",
+                   "schedule": what["schedule"], "cache_policy": what["cache_policy"],
                    "autotune_ms_best_and_per_chunk": [round(x, 5) for x in tuned[0]] if tuned else None,
-                   "table_bytes": table_bytes, "algorithmic_bytes_per_param": bpp},
+                   "table_bytes": what["table_bytes"], "algorithmic_bytes_per_param": bpp},
         "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(gbs / HBM_PEAK_GBS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.index) if (args.chunk_elems == 0 and not args.in_place and not args.flat
-                                                                         and args.grad_dtype == "f16" and args.schedule == "auto"
-                                                                         and args.workgroups == 0) else None,
-                     "kernel": ("fused_adam%s_kernel<R=%d>" % ("_ordered" if ordered else "", R)) if cfg.optimizer == "adam"
-                     else "lamb_phase1%s_kernel + lamb_phase2%s_kernel" % (("_ordered",) * 2 if ordered else ("", "")),
-                     "bytes_per_launch": bpp * N, "avg_launch_ms": round(ms, 5)},
+                     "traffic": traffic[0] if traffic else None,
+                     "traffic_source": ("constant from %s (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by the copy kernel); "
+                                        "not measured by this run" % traffic[1]) if traffic else None,
+                     "kernel": what["kernel"], "bytes_per_launch": bpp * N, "avg_launch_ms": round(ms, 5)},
     }
 
     if not args.no_extras:
         extras = {}
+        t_next = timer.t
         # the same K steps with the flag read back (and the commit decided) after every step
         for _ in range(3):
-            shard.step(headline_fn, hyper(t_next)); t_next += 1
+            shard.step(headline_fn, timer.hyper(t_next)); t_next += 1
         torch.cuda.synchronize()
         w0 = time.perf_counter()
         for _ in range(K):
-            assert shard.step(headline_fn, hyper(t_next)) == 0
+            assert shard.step(headline_fn, timer.hyper(t_next)) == 0
             t_next += 1
         extras["ms_per_step_with_flag_readback"] = round((time.perf_counter() - w0) * 1e3 / K, 5)
         extras["wall_ms_per_step_enqueue_only_loop"] = round(wall * 1e3 / (K + Wm), 5)
+        timer.t = t_next
 
-        def rate(fn, bytes_pp, steps):
-            m, f, _ = timed(fn, steps, max(2, Wm // 2), t0=t_next)
-            assert f == 0
-            return {"ms_per_step": round(m, 5), "GB/s": round(bytes_pp * N / (m * 1e-3) / 1e9, 1),
-                    "params_per_sec": round(N / (m * 1e-3), 1), "algorithmic_bytes_per_param": bytes_pp}
         ks = max(5, K // 4)
         if args.graph:
             ks = max(20, ks // 20 * 20)
+        wk = max(2, Wm // 2)
         if cfg.optimizer == "adam":
-            extras["fused_lamb_same_list"] = rate(cc.cc_fused_lamb_step, lamb_bytes_per_param(R), ks) if not args.in_place else None
+            extras["fused_lamb_same_list"] = rate(timer.run(cc.cc_fused_lamb_step, ks, wk, args.graph), lamb_bytes_per_param(R, gb), N) if not args.in_place else None
         else:
-            extras["fused_adam_same_list"] = rate(cc.cc_fused_adam_step, adam_bytes_per_param(R), ks)
-        extras["unfused_adam"] = rate(cc.cc_unfused_adam_step, unfused_adam_bytes_per_param(R), ks)
+            extras["fused_adam_same_list"] = rate(timer.run(cc.cc_fused_adam_step, ks, wk, args.graph), adam_bytes_per_param(R, gb), N)
+        extras["unfused_adam"] = rate(timer.run(cc.cc_unfused_adam_step, ks, wk, args.graph), unfused_adam_bytes_per_param(R, gb), N)
         if args.grad_dtype == "f16":          # reduce 2R + 2, optimizer 14 + 12, cast 4 + 2
-            extras["unfused_adam_fp16_intermediate"] = rate(
-                lambda p, h, f, st=None: cc.cc_unfused_adam_step_ex(p, h, f, st, cc.CC_GRAD_F16), 2 * R + 34, ks)
+            extras["unfused_adam_fp16_intermediate"] = rate(timer.run(
+                lambda p, h, f, st=None: cc.cc_unfused_adam_step_ex(p, h, f, st, cc.CC_GRAD_F16), ks, wk, args.graph), 2 * R + 34, N)
         if not args.in_place:
-            extras["unfused_lamb"] = rate(cc.cc_unfused_lamb_step, unfused_lamb_bytes_per_param(R), ks)
+            extras["unfused_lamb"] = rate(timer.run(cc.cc_unfused_lamb_step, ks, wk, args.graph), unfused_lamb_bytes_per_param(R, gb), N)
         fa = extras.get("fused_adam_same_list", {"ms_per_step": ms})["ms_per_step"] if cfg.optimizer != "adam" else ms
         extras["fused_vs_unfused_adam_speedup"] = round(extras["unfused_adam"]["ms_per_step"] / fa, 3)
+
+        out["cpu_baseline"] = cpu_baseline(shard, cfg, timer.hyper(1), args.cpu_seconds)
+        shard.destroy()
+        del shard, timer
+        torch.cuda.empty_cache()
 
         # plain copy kernel: the practical streaming ceiling of this machine (bytes counted once read + once written)
         nbytes = 2 << 30
         src = torch.empty(nbytes, dtype=torch.uint8, device=dev).fill_(1)
         dst = torch.empty(nbytes, dtype=torch.uint8, device=dev)
-        if bpp * N < (256 << 20):
-            # the whole step fits the 256 MB Infinity Cache, so the timed loop above ran cache-resident; this is the
-            # same step with the caches evicted first (a 2 GiB copy), timed one step at a time
-            cold = []
-            for _ in range(30):
-                cc.cc_copy_probe(dst, src, nbytes)
-                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                a.record()
-                shard.run(headline_fn, hyper(t_next))
-                b.record()
-                shard.commit()
-                t_next += 1
-                torch.cuda.synchronize()
-                cold.append(a.elapsed_time(b))
-            cold.sort()
-            extras["cold_cache_ms_per_step_median"] = round(cold[len(cold) // 2], 5)
-            extras["cold_cache_GB/s"] = round(bpp * N / (cold[len(cold) // 2] * 1e-3) / 1e9, 1)
         for _ in range(3):
             cc.cc_copy_probe(dst, src, nbytes)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -268,6 +320,43 @@ def main() -> int:
         e1.record()
         torch.cuda.synchronize()
         extras["copy_kernel_GB/s"] = round(2 * nbytes / (e0.elapsed_time(e1) / 20 * 1e-3) / 1e9, 1)
+
+        # ---- the other configurations, default options, same timing method ---------------------------------------
+        if default_options and not args.graph:
+            others = {}
+            for index in (1, 3, 4, 5):
+                if index == cfg.index:
+                    continue
+                c2, s2 = make(index, options=False)
+                t2 = Timer(torch, cc, s2, c2)
+                fn2 = cc.cc_fused_adam_step if c2.optimizer == "adam" else cc.cc_fused_lamb_step
+                b2 = adam_bytes_per_param(c2.R) if c2.optimizer == "adam" else lamb_bytes_per_param(c2.R)
+                rec = {"workload": "config %d: fused %s, %s, T=%d, N=%d, R=%d" % (index, c2.optimizer, WORKLOAD_NAMES[index],
+                                                                                  len(c2.params), c2.numel, c2.R)}
+                rec.update(describe(cc, s2, c2.R, c2.optimizer, False))
+                if b2 * c2.numel < (256 << 20):
+                    # the whole step fits the 256 MB Infinity Cache: consecutive steps run cache-resident, and an eager
+                    # launch loop measures the Python caller; so all four combinations are reported
+                    rec["warm_cache_hip_graph_replay"] = rate(t2.run(fn2, 4000, 400, graph=True), b2, c2.numel)
+                    rec["warm_cache_eager_launches"] = rate(t2.run(fn2, 2000, 200), b2, c2.numel)
+                    rec["cold_cache_single_step"] = rate(t2.cold(fn2, lambda: cc.cc_copy_probe(dst, src, nbytes)), b2, c2.numel)
+                    rec["note"] = ("cache-resident: GB/s here is not HBM bandwidth; cold = caches evicted by a 2 GiB copy before "
+                                   "every step, the event pair brackets the step alone (launch mode does not enter)")
+                    rec.update(rec["warm_cache_hip_graph_replay"])
+                    rec["launch"] = "hip graph replay"
+                else:
+                    n2 = max(10, min(K, int(400.0 / (b2 * c2.numel / 6.4e12 * 1e3))))   # about 0.4 s of steps
+                    rec.update(rate(t2.run(fn2, n2, max(3, n2 // 8)), b2, c2.numel))
+                    rec["launch"] = "eager"
+                    rec["steps"] = n2
+                tr = MEASURED_TRAFFIC.get(index)
+                rec["traffic"] = tr[0] if tr else None
+                rec["traffic_source"] = ("constant from %s; not measured by this run" % tr[1]) if tr else None
+                others["config%d" % index] = rec
+                s2.destroy()
+                del s2, t2
+                torch.cuda.empty_cache()
+            extras["configs"] = others
         del src, dst
         cus, clk_khz, bus_bits, total_bytes = cc.cc_device_info()
         extras["device"] = {"name": torch.cuda.get_device_name(0), "compute_units": cus, "memory_clock_khz": clk_khz,
@@ -276,10 +365,9 @@ def main() -> int:
                             # 8192 pins x 8 Gb/s / 8 = 8192 GB/s, the published 8 TB/s
                             "GB/s_at_4_transfers_per_clock": round(4 * clk_khz * 1e3 * bus_bits / 8 / 1e9, 1)}
         out["extras"] = extras
+    else:
+        shard.destroy()
 
-        out["cpu_baseline"] = cpu_baseline(shard, cfg, hyper(1), args.cpu_seconds)
-
-    shard.destroy()
     print(json.dumps(out), flush=True)
     return 0
 
