@@ -165,8 +165,9 @@ int cc_plan_layout(const cc_plan *plan, int32_t *chunk_elems, int32_t *block_thr
 /*
  * Cache policy of the streaming kernels' accesses.  STREAMING marks every access non-temporal (right for shards
  * that do not fit on chip).  RESIDENT uses plain accesses, so that a shard whose whole step fits the 256 MB Infinity
- * Cache finds its inputs on chip in the next step; it exists for 128-thread workgroups (chunks below 4096 elements)
- * and is ignored otherwise.  AUTO (default) picks RESIDENT when the step's buffers total less than 192 MiB.
+ * Cache may find its inputs on chip in the next step; it exists for 128-thread workgroups (chunks below 4096 elements)
+ * and is ignored otherwise.  Which of the two is faster on a cache-resident shard differed from machine to machine,
+ * so AUTO (default) is STREAMING and cc_plan_autotune tries both.
  */
 typedef enum cc_cache_policy { CC_CACHE_AUTO = 0, CC_CACHE_STREAMING = 1, CC_CACHE_RESIDENT = 2 } cc_cache_policy;
 int cc_plan_set_cache_policy(cc_plan *plan, int32_t policy);
@@ -266,11 +267,6 @@ typedef struct cc_epilogue {
     uint16_t       *out;                   /* numel fp16 */
     float           dropout_p;
     uint64_t        seed;
-    void           *workspace;             /* NULL, or 256 bytes of device memory (256-byte aligned) that are zero before
-                                              the first call and that every call leaves zero: slices of 4 Mi elements and
-                                              more then run under the ordered persistent schedule (cc_plan_set_schedule).
-                                              Calls that share a workspace must not overlap in time.  Ignored by
-                                              cc_unfused_epilogue. */
 } cc_epilogue;
 
 /* One pass: 2R + 4 bytes per element. */

@@ -45,7 +45,7 @@ class cc_hparams(C.Structure):
 class cc_epilogue(C.Structure):
     _fields_ = [("numel", C.c_uint64), ("first", C.c_uint64), ("hidden", C.c_uint32), ("R", C.c_int32),
                 ("partial", C.c_void_p * CC_MAX_R), ("bias", C.c_void_p), ("residual", C.c_void_p), ("out", C.c_void_p),
-                ("dropout_p", C.c_float), ("seed", C.c_uint64), ("workspace", C.c_void_p)]
+                ("dropout_p", C.c_float), ("seed", C.c_uint64)]
 
 
 # every symbol include/ccfused.h declares
@@ -331,8 +331,7 @@ def cc_lamb_norms_read(plan: Plan, T: int, stream=None):
     return [(buf[2 * i], buf[2 * i + 1]) for i in range(T)]
 
 
-def _epilogue(partials, bias, residual, out, first: int, hidden: int, dropout_p: float, seed: int, numel=None,
-              workspace=None) -> cc_epilogue:
+def _epilogue(partials, bias, residual, out, first: int, hidden: int, dropout_p: float, seed: int, numel=None) -> cc_epilogue:
     e = cc_epilogue()
     e.numel = residual.numel() if numel is None else numel
     e.first, e.hidden, e.R = first, hidden, len(partials)
@@ -340,13 +339,12 @@ def _epilogue(partials, bias, residual, out, first: int, hidden: int, dropout_p:
         e.partial[r] = _ptr(x)
     e.bias, e.residual, e.out = _ptr(bias), _ptr(residual), _ptr(out)
     e.dropout_p, e.seed = dropout_p, seed
-    e.workspace = _ptr(workspace)
     return e
 
 
 def cc_fused_epilogue(partials, bias, residual, out, first: int, hidden: int, dropout_p: float, seed: int, stream=None,
-                      numel=None, workspace=None) -> None:
-    e = _epilogue(partials, bias, residual, out, first, hidden, dropout_p, seed, numel, workspace)
+                      numel=None) -> None:
+    e = _epilogue(partials, bias, residual, out, first, hidden, dropout_p, seed, numel)
     _check(load().cc_fused_epilogue(C.byref(e), _stream(stream)))
 
 

@@ -1,7 +1,8 @@
 """Builds libccfused.so for gfx950 with hipcc, in-tree (next to this file).
 
 The library is several translation units (one per kernel family) only so that they compile side by side; each is
-compiled to an object file and the objects are linked into one shared library."""
+compiled to an object file and the objects are linked into one shared library, whose dynamic symbol table is cut down
+to the C ABI by csrc/exports.map."""
 from __future__ import annotations
 
 import os
@@ -14,7 +15,9 @@ ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
 SOURCES = [os.path.join(CSRC, n) for n in ("ccfused.hip", "launch_adam_f16.hip", "launch_adam_f32.hip", "launch_lamb.hip",
                                            "launch_unfused.hip")]
-DEPS = SOURCES + [os.path.join(CSRC, "kernels.hip.h"), os.path.join(CSRC, "plan.hpp"), os.path.join(ROOT, "include", "ccfused.h")]
+EXPORTS_MAP = os.path.join(CSRC, "exports.map")
+DEPS = SOURCES + [os.path.join(CSRC, "kernels.hip.h"), os.path.join(CSRC, "plan.hpp"), os.path.join(CSRC, "launch_adam.inc.hpp"),
+                  os.path.join(ROOT, "include", "ccfused.h"), EXPORTS_MAP]
 LIB = os.path.join(_HERE, "libccfused.so")
 OBJ_DIR = os.path.join(_HERE, "_build")
 
@@ -54,7 +57,8 @@ def build_library(force: bool = True, extra=()) -> str:
         with ThreadPoolExecutor(max_workers=min(len(SOURCES), os.cpu_count() or 1)) as pool:
             list(pool.map(compile_one, zip(SOURCES, objs)))
         tmp = LIB + ".tmp%d" % os.getpid()
-        subprocess.check_call([HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", tmp] + objs)
+        subprocess.check_call([HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", "-Wl,--version-script=" + EXPORTS_MAP,
+                               "-o", tmp] + objs)
         os.replace(tmp, LIB)
     finally:
         for obj in objs:

@@ -110,12 +110,6 @@ int check_overlaps(const cc_tensor *tensors, int32_t T, int32_t R, size_t grad_b
     return CC_OK;
 }
 
-// Buffers a step touches: R gradient slices, both copies of w, m, v (one if in place) and the fp16 weights.
-uint64_t step_footprint_bytes(const cc_plan *p)
-{
-    return p->numel * ((p->grad_f32 ? 4u : 2u) * (uint64_t)p->R + 12u + 14u);
-}
-
 // Settles what the step calls will use (layout, schedule, cache policy) from what the caller asked for.
 void resolve_schedule(cc_plan *p)
 {
@@ -129,10 +123,10 @@ void resolve_schedule(cc_plan *p)
     else if (p->schedule == CC_SCHEDULE_PER_CHUNK) p->ordered = false;
     else p->ordered = L.chunks >= kOrderedMinChunksPerCu * (int64_t)p->cus && !(p->grad_f32 && p->R > kOrderedMaxF32Slices);
     if (L.chunk_elems != kDefaultChunkElems || L.chunks == 0) p->ordered = false;
-    if (p->cache_policy == CC_CACHE_RESIDENT) p->resident = true;
-    else if (p->cache_policy == CC_CACHE_STREAMING) p->resident = false;
-    else p->resident = step_footprint_bytes(p) < kResidentMaxBytes;
-    if (L.block != kSmallBlock || p->ordered) p->resident = false;
+    // AUTO keeps the non-temporal hints: on cache-resident shards plain accesses were faster on some machines of the
+    // pool and slower on others (2^20 elements, R = 4: 5.1 against 5.4 us on one, 6.6 against 6.0 us on another), so
+    // the choice is left to the caller and to cc_plan_autotune
+    p->resident = p->cache_policy == CC_CACHE_RESIDENT && L.block == kSmallBlock && !p->ordered;
 }
 
 void free_layout(Layout &L)
@@ -656,7 +650,6 @@ int check_epilogue(const cc_epilogue *e, EpilogueArgs *a)
 
 constexpr int kEpilogueBlock = 512;
 constexpr uint32_t kEpilogueChunk = kEpilogueBlock * 8 * 2;
-constexpr uint64_t kEpilogueOrderedMinElems = 4u << 20;     // below this the ordered schedule's fixed latency does not pay
 
 int epilogue_grid(uint64_t numel, uint32_t chunk, unsigned *grid)
 {
@@ -677,23 +670,6 @@ int cc_fused_epilogue(const cc_epilogue *e, void *stream)
     unsigned grid;
     if ((rc = epilogue_grid(e->numel, kEpilogueChunk, &grid))) return rc;
     hipStream_t st = (hipStream_t)stream;
-    if (e->workspace && (reinterpret_cast<uintptr_t>(e->workspace) & 255u) != 0)
-        return fail(CC_ERR_ALIGN, "epilogue: workspace is not 256-byte aligned");
-    if (e->workspace && e->numel >= kEpilogueOrderedMinElems) {
-        int dev = 0, cus = 0;
-        HIP_TRY(hipGetDevice(&dev));
-        HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
-        unsigned wgs = cus > 0 ? (unsigned)cus : 1u;
-        if (wgs > (grid + 1) / 2) wgs = (grid + 1) / 2;
-        const uint32_t nfull = (uint32_t)(e->numel / kEpilogueChunk);
-        WorkQueue *q = (WorkQueue *)e->workspace;
-        switch (e->R) {
-#define CASE(r) case r: hipLaunchKernelGGL((fused_epilogue_ordered_kernel<r, kEpilogueBlock>), dim3(wgs), dim3(kEpilogueBlock), 0, st, a, nfull, grid, 1u, q); break;
-            FOR_EACH_R(CASE)
-#undef CASE
-        }
-        return launched("fused_epilogue_ordered_kernel");
-    }
     switch (e->R) {
 #define CASE(r) case r: hipLaunchKernelGGL((fused_epilogue_kernel<r, kEpilogueBlock>), dim3(grid), dim3(kEpilogueBlock), 0, st, a); break;
         FOR_EACH_R(CASE)

@@ -110,9 +110,10 @@ __device__ __forceinline__ gbytes chunk_base(void *p, uint64_t byte_off) { retur
 //   Streaming: non-temporal hints on every access.  Right for shards that do not fit on chip: the data is not touched
 //              again before it has left every cache (+3 % with one workgroup per chunk, +7 % on the stores under the
 //              ordered schedule).
-//   Resident:  plain accesses.  Right for shards whose whole step (inputs and outputs of two consecutive steps, which
-//              ping-pong between two copies) fits the 256 MB Infinity Cache: the next step then finds what this one
-//              wrote on chip.  Measured on the memory pattern of a 2^20-element step: 5.0 us against 5.8 us.
+//   Resident:  plain accesses, for shards whose whole step (inputs and outputs of two consecutive steps, which
+//              ping-pong between two copies) fits the 256 MB Infinity Cache.  On the memory pattern of a 2^20-element
+//              step they were 0.3-0.8 us faster than non-temporal ones on some machines and 0.3-0.6 us slower on
+//              others, so plans use them only on request (or when the tuner measures them faster).
 struct Streaming { static constexpr bool kNonTemporal = true; };
 struct Resident { static constexpr bool kNonTemporal = false; };
 
@@ -195,67 +196,126 @@ __device__ __forceinline__ Where locate(const DevTensor *__restrict__ tensors, c
     return locate_at(tensors, chunks, blockIdx.x, chunk_elems);
 }
 
-// The overflow flag is produced by the same launch that does the work, with no clearing launch in front of it.
-// A 64-bit word carries two facts at once: the low half counts finished workgroups, the high half counts
-// workgroups that saw an inf/NaN.  Each workgroup adds its contribution with ONE relaxed atomic; because both
-// halves travel in the same read-modify-write, no fence has to order anything (a device-scope fence writes the
-// L2 back on every workgroup: measured 2.8x slower).  Atomics on one address serialize, and a small grid ends all
-// at once, so the count is kept in two levels: workgroup b adds to slot b % 64 (each slot on its own 128-byte
-// line), and the workgroup that completes a slot carries the slot's result to the top word.  The workgroup that
-// completes the top word stores 0 or 1 to the caller's flag (written exactly once per launch).  Whoever completes
-// a word also zeroes it for the next launch.  Nothing waits on anything.
-constexpr uint32_t kFlagSlots = 64;
+// The overflow flag is produced by the same launch that does the work, with no clearing launch in front of it and
+// with nothing on the path between a wave's loads and its stores.
+//
+// What has to happen: the caller's flag must read 0 after a launch in which no wave saw an inf/NaN and 1 otherwise,
+// and the scratch words must be ready for the next launch.  Counting FINISHED workgroups (the obvious way to find
+// "the last one", who then writes the flag) puts two dependent atomic round trips behind the last wave's loads, and a
+// returning atomic issued after the stores is only seen once those stores are acknowledged (the memory counter is
+// in order): measured 0.9-1.7 us on a 6 us step.  So ARRIVALS are counted instead:
+//
+//   * Lane 0 of every wave adds 1 to one of kFlagSlots slot words as its very first act, before any load.  The
+//     result comes back while the loads are in flight.  The high half of a slot word is the launch's phase p (the
+//     same in every slot between launches), so the one atomic tells a wave p and whether it is the last arrival in
+//     its slot.  That wave puts the slot back to (p+1, 0) and adds 1 to the top word; the wave that completes the top
+//     word is the last arrival of the launch: every wave has arrived, none will touch the counters again, so it can
+//     zero the top word and move the slots this launch did not use to p+1 as well.
+//   * The last arrival clears the caller's flag with a returning exchange issued before its own update and stores,
+//     and, behind its stores, once that exchange has returned (so the 0 has been performed at the device's coherence
+//     point), exchanges the state word to (p+1, CLEARED).  If this second exchange returns (p+1, BAD), a wave had
+//     reported an inf/NaN before, and the last arrival sets the flag to 1 itself.  (A release on the second exchange
+//     would state the same order in the language's terms, but costs a write-back of the whole L2 in the middle of
+//     the kernel on the one wave that everybody ends up waiting for: measured +0.7 to +1.3 us per step.  The order is
+//     enforced in the source instead: the second exchange takes an operand that depends on the first one's result.)
+//   * A wave that saw an inf/NaN (rare) moves the state word to (p+1, BAD) with a compare-exchange loop, unless it
+//     finds (p+1, CLEARED) there: then the flag's 0 was performed before, and it stores 1 into the flag itself.
+//     Either the last arrival's exchange comes first in the state word's modification order, and the reporting wave
+//     sees CLEARED and writes 1 after the 0; or the report comes first, and the exchange returns it.  Both can write 1.
+//   * Values of older launches in the state word carry another phase and are ignored, so nothing has to be reset at
+//     the end of a launch, which is what would need a count of finished waves.
+//
+// Nothing waits on another wave.  Per launch every wave issues one atomic; one wave per slot issues three more; one
+// wave issues the handful around the flag.  Phases are 32 bits and wrap; a report that is exactly 2^32 launches old
+// would be taken for a new one.
+constexpr uint32_t kFlagSlots = 128;
 struct FlagScratch {
-    struct alignas(128) Line { unsigned long long word; } slot[kFlagSlots], top;
+    struct alignas(128) Line { unsigned long long word; } slot[kFlagSlots], top, state;
 };
-
-// The count is taken in two steps so that the first atomic's round trip can pass under the workgroup's arithmetic:
-// publish_begin (after the sums, which decide `bad`) issues it, publish_end (after the stores) looks at what came back.
-struct FlagTicket { unsigned long long mine, prev; };
+constexpr unsigned long long kStateBad = 1ull, kStateCleared = 2ull;
 
 template <int BLOCK>
-__device__ __forceinline__ FlagTicket publish_begin(bool bad, FlagScratch *fs)
-{
-    const int any = BLOCK > 64 ? __syncthreads_or(bad ? 1 : 0) : (__builtin_amdgcn_ballot_w64(bad) != 0ull ? 1 : 0);
-    FlagTicket t;
-    t.mine = 1ull | (any ? (1ull << 32) : 0ull);
-    t.prev = 0ull;
-    if (threadIdx.x == 0)
-        t.prev = atomicAdd(gridDim.x <= kFlagSlots ? &fs->top.word : &fs->slot[blockIdx.x % kFlagSlots].word, t.mine);
-    return t;
-}
+struct FlagCount {
+    unsigned long long prev = 0ull, tprev = 0ull;
+    uint32_t slot = 0, in_slot = 0, used = 0;
+    int32_t flag_before = 0;
+    bool slot_last = false, launch_last = false;
 
-__device__ __forceinline__ void publish_end(const FlagTicket &t, FlagScratch *fs, int32_t *flag)
-{
-    if (threadIdx.x == 0) {
-        const unsigned long long mine = t.mine, prev = t.prev;
-        if (gridDim.x <= kFlagSlots) {                  // few workgroups: counted on the top word directly
-            if ((uint32_t)prev == gridDim.x - 1) {
-                *flag = ((prev + mine) >> 32) != 0ull ? 1 : 0;
-                atomicExch(&fs->top.word, 0ull);
-            }
-            return;
+    __device__ __forceinline__ bool counting_lane() const { return (threadIdx.x & 63u) == 0u; }
+    __device__ __forceinline__ uint32_t tag() const { return (uint32_t)(prev >> 32) + 1u; }          // this launch's p + 1
+
+    // First act of a kernel: the wave's arrival.  Nothing is waited for here.
+    __device__ __forceinline__ void arrive(FlagScratch *fs)
+    {
+        if (counting_lane()) {
+            constexpr uint32_t kWaves = BLOCK / 64;
+            const uint32_t waves = gridDim.x * kWaves;
+            const uint32_t me = blockIdx.x * kWaves + (threadIdx.x >> 6);
+            slot = me % kFlagSlots;
+            in_slot = (waves - slot + kFlagSlots - 1) / kFlagSlots;      // waves w with w % kFlagSlots == slot
+            used = waves < kFlagSlots ? waves : kFlagSlots;
+            prev = atomicAdd(&fs->slot[slot].word, 1ull);
         }
-        const uint32_t slot = blockIdx.x % kFlagSlots;
-        const uint32_t in_slot = (gridDim.x - slot + kFlagSlots - 1) / kFlagSlots;      // workgroups b with b % 64 == slot
-        const uint32_t slots_used = gridDim.x < kFlagSlots ? gridDim.x : kFlagSlots;
-        if ((uint32_t)prev == in_slot - 1) {            // this workgroup completed its slot
-            atomicExch(&fs->slot[slot].word, 0ull);
-            const unsigned long long up = 1ull | (((prev + mine) >> 32) != 0ull ? (1ull << 32) : 0ull);
-            const unsigned long long tprev = atomicAdd(&fs->top.word, up);
-            if ((uint32_t)tprev == slots_used - 1) {    // ... and the top word
-                *flag = ((tprev + up) >> 32) != 0ull ? 1 : 0;
-                atomicExch(&fs->top.word, 0ull);
+    }
+    // Once the arrival's result is needed (behind the issue of the loads): the last arrival in a slot moves on to the top word.
+    __device__ __forceinline__ void slot_level(FlagScratch *fs)
+    {
+        if (counting_lane()) {
+            slot_last = (uint32_t)prev == in_slot - 1;
+            if (slot_last) {
+                atomicExch(&fs->slot[slot].word, (unsigned long long)tag() << 32);
+                tprev = atomicAdd(&fs->top.word, 1ull);
             }
         }
     }
-}
-
-template <int BLOCK>
-__device__ __forceinline__ void publish_flag(bool bad, FlagScratch *fs, int32_t *flag)
-{
-    publish_end(publish_begin<BLOCK>(bad, fs), fs, flag);
-}
+    // Before the wave's stores: the last arrival of the launch tidies the counters and starts clearing the flag.
+    __device__ __forceinline__ void top_level(FlagScratch *fs, int32_t *flag)
+    {
+        if (counting_lane() && slot_last) {
+            launch_last = (uint32_t)tprev == used - 1;
+            if (launch_last) {
+                atomicExch(&fs->top.word, 0ull);
+                for (uint32_t k = used; k < kFlagSlots; ++k) atomicExch(&fs->slot[k].word, (unsigned long long)tag() << 32);
+                flag_before = __hip_atomic_exchange(flag, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+    }
+    // After the wave's stores have been issued: reports.
+    __device__ __forceinline__ void finish(bool bad, FlagScratch *fs, int32_t *flag)
+    {
+        const bool any = __builtin_amdgcn_ballot_w64(bad) != 0ull;
+        if (counting_lane()) {
+            const unsigned long long mine_bad = ((unsigned long long)tag() << 2) | kStateBad;
+            const unsigned long long cleared = ((unsigned long long)tag() << 2) | kStateCleared;
+            if (launch_last) {
+                unsigned long long mark = cleared;
+                asm volatile("" : "+v"(mark) : "v"(flag_before));     // not before the flag's exchange has returned
+                const unsigned long long sprev = __hip_atomic_exchange(&fs->state.word, mark, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (sprev == mine_bad) __hip_atomic_store(flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            if (any) {
+                unsigned long long cur = __hip_atomic_load(&fs->state.word, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
+                while (true) {
+                    if (cur == cleared) {                 // the flag was cleared before: this store comes after the 0
+                        __hip_atomic_store(flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        break;
+                    }
+                    if (cur == mine_bad) break;           // another wave has reported for this launch already
+                    if (__hip_atomic_compare_exchange_strong(&fs->state.word, &cur, mine_bad, __ATOMIC_ACQ_REL, __ATOMIC_ACQUIRE,
+                                                             __HIP_MEMORY_SCOPE_AGENT))
+                        break;                            // the last arrival's exchange will return this report
+                }
+            }
+        }
+    }
+    // Everything behind the arrival at once, for kernels that do not place the stages themselves.
+    __device__ __forceinline__ void settle(bool bad, FlagScratch *fs, int32_t *flag)
+    {
+        slot_level(fs);
+        top_level(fs, flag);
+        finish(bad, fs, flag);
+    }
+};
 
 // Only for a plan without any chunk: nothing else would write the flag.
 [[maybe_unused]] static __global__ void clear_flag_kernel(int32_t *flag) { *flag = 0; }
@@ -301,12 +361,12 @@ __device__ __forceinline__ void stream_chunk(Op &op, uint32_t len)
     }
 }
 
-// One workgroup per chunk, for an Op that raises the flag and splits compute into reduce + update: when the chunk
-// is exactly one sweep (the launch shapes the plans use), the count for the flag is started as soon as the sums
-// are known, so that the atomic's latency passes under the update arithmetic instead of behind the stores.  That
-// is worth ~0.5 us on a shard that is one wave of workgroups deep.
+// One workgroup per chunk, for an Op that raises the flag.  `fc` has arrived already (first act of the kernel).  When
+// the chunk is exactly one sweep (the launch shapes the plans use), the stages of the count are placed where their
+// results are free: the slot level behind the issue of the loads, the top level behind the sums, the reports behind
+// the stores.  The waves of a workgroup never wait for each other here.
 template <int BLOCK, int GROUPS, class Op>
-__device__ __forceinline__ void sweep_and_publish(Op &op, uint32_t len, FlagScratch *fs, int32_t *flag)
+__device__ __forceinline__ void sweep_and_publish(Op &op, uint32_t len, FlagCount<BLOCK> &fc, FlagScratch *fs, int32_t *flag)
 {
     constexpr uint32_t kGroup = BLOCK * Op::kPack;
     if (len == GROUPS * kGroup) {
@@ -315,17 +375,19 @@ __device__ __forceinline__ void sweep_and_publish(Op &op, uint32_t len, FlagScra
 #pragma unroll
         for (int g = 0; g < GROUPS; ++g) op.load(x[g], g * kGroup + lane_e);
         __builtin_amdgcn_sched_barrier(0);
+        fc.slot_level(fs);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int g = 0; g < GROUPS; ++g) op.reduce(x[g]);
-        const FlagTicket t = publish_begin<BLOCK>(op.bad, fs);
+        fc.top_level(fs, flag);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int g = 0; g < GROUPS; ++g) { op.update(x[g]); op.store(x[g], g * kGroup + lane_e); }
         __builtin_amdgcn_sched_barrier(0);
-        publish_end(t, fs, flag);
+        fc.finish(op.bad, fs, flag);
     } else {
         stream_chunk<BLOCK, Op, GROUPS>(op, len);
-        publish_flag<BLOCK>(op.bad, fs, flag);
+        fc.settle(op.bad, fs, flag);
     }
 }
 
@@ -640,10 +702,12 @@ __global__ __launch_bounds__(BLOCK) void fused_adam_kernel(const DevTensor *__re
                                                            const Chunk *__restrict__ chunks, StepScalars s,
                                                            FlagScratch *__restrict__ fs, int32_t *__restrict__ flag)
 {
+    FlagCount<BLOCK> fc;
+    fc.arrive(fs);
     const Where wh = locate(tensors, chunks, s.chunk_elems);
     AdamOp<GradSlices<R, GF32, Mem>, MODE, true> op;
     op.init(wh.t, wh.base, s);
-    sweep_and_publish<BLOCK, GROUPS>(op, wh.len, fs, flag);
+    sweep_and_publish<BLOCK, GROUPS>(op, wh.len, fc, fs, flag);
 }
 
 // A plan with a single tensor (the contiguous case of Table 2 and of the standalone sweep of Section 6.1.1) needs
@@ -654,11 +718,13 @@ template <int R, int MODE, int BLOCK, bool GF32 = false, int GROUPS = 2, class M
 __global__ __launch_bounds__(BLOCK) void fused_adam_flat_kernel(DevTensor t, StepScalars s, FlagScratch *__restrict__ fs,
                                                                 int32_t *__restrict__ flag)
 {
+    FlagCount<BLOCK> fc;
+    fc.arrive(fs);
     const uint64_t base = (uint64_t)blockIdx.x * s.chunk_elems;
     const uint64_t rem = t.numel - base;
     AdamOp<GradSlices<R, GF32, Mem>, MODE, true> op;
     op.init(&t, base, s);
-    sweep_and_publish<BLOCK, GROUPS>(op, rem < s.chunk_elems ? (uint32_t)rem : s.chunk_elems, fs, flag);
+    sweep_and_publish<BLOCK, GROUPS>(op, rem < s.chunk_elems ? (uint32_t)rem : s.chunk_elems, fc, fs, flag);
 }
 
 // The same step under the ordered persistent schedule (chunk_elems == BLOCK * 4 * GROUPS).
@@ -824,12 +890,14 @@ __device__ __forceinline__ void lamb_phase1_body(const DevTensor *__restrict__ t
                                                  const StepScalars &s, double *__restrict__ partials,
                                                  FlagScratch *__restrict__ fs, int32_t *__restrict__ flag)
 {
+    FlagCount<BLOCK> fc;
+    if (RAISE) fc.arrive(fs);
     const Where wh = locate(tensors, chunks, s.chunk_elems);
     LambPhase1Op<Grad> op;
     op.init(wh.t, wh.base, s);
     op.partials = partials;
     if (RAISE) {
-        sweep_and_publish<BLOCK, 2>(op, wh.len, fs, flag);
+        sweep_and_publish<BLOCK, 2>(op, wh.len, fc, fs, flag);
     } else {
         stream_chunk<BLOCK>(op, wh.len);
     }
@@ -1041,11 +1109,13 @@ __global__ __launch_bounds__(BLOCK) void reduce_kernel(const DevTensor *__restri
                                                        const Chunk *__restrict__ chunks, StepScalars s,
                                                        FlagScratch *__restrict__ fs, int32_t *__restrict__ flag)
 {
+    FlagCount<BLOCK> fc;
+    fc.arrive(fs);
     const Where wh = locate(tensors, chunks, s.chunk_elems);
     ReduceOp<R, GF32, Mem> op;
     op.init(wh.t, wh.base);
     stream_chunk<BLOCK>(op, wh.len);
-    publish_flag<BLOCK>(op.bad, fs, flag);
+    fc.settle(op.bad, fs, flag);
 }
 
 template <int R, int BLOCK, bool GF32 = false>
@@ -1113,11 +1183,13 @@ __global__ __launch_bounds__(BLOCK) void reduce_half_kernel(const DevTensor *__r
                                                             const Chunk *__restrict__ chunks, StepScalars s,
                                                             FlagScratch *__restrict__ fs, int32_t *__restrict__ flag)
 {
+    FlagCount<BLOCK> fc;
+    fc.arrive(fs);
     const Where wh = locate(tensors, chunks, s.chunk_elems);
     ReduceHalfOp<R, Mem> op;
     op.init(wh.t, wh.base);
     stream_chunk<BLOCK>(op, wh.len);
-    publish_flag<BLOCK>(op.bad, fs, flag);
+    fc.settle(op.bad, fs, flag);
 }
 
 template <int R, int BLOCK>
@@ -1315,7 +1387,6 @@ struct FusedEpilogueOp {
         for (int r = 1; r < R; ++r) sum += ld_f16(part[r], j * 2);
         t.single(j, sum);
     }
-    template <int BLOCK> __device__ __forceinline__ void end_chunk(uint32_t) {}
 };
 
 template <int R, int BLOCK>
@@ -1327,30 +1398,6 @@ __global__ __launch_bounds__(BLOCK) void fused_epilogue_kernel(EpilogueArgs a)
     FusedEpilogueOp<R> op;
     op.init(a, base);
     stream_chunk<BLOCK>(op, rem < kChunk ? (uint32_t)rem : kChunk);
-}
-
-// The same pass under the ordered persistent schedule: the slice is one contiguous range, so chunk c is simply
-// elements [c kChunk, (c+1) kChunk) and no table is needed; only the last chunk can be short.
-template <int R, int BLOCK>
-__global__ __launch_bounds__(BLOCK) void fused_epilogue_ordered_kernel(EpilogueArgs a, uint32_t nfull, uint32_t nchunks,
-                                                                       uint32_t span, WorkQueue *__restrict__ q)
-{
-    constexpr uint32_t kChunk = BLOCK * 8 * 2;
-    typedef FusedEpilogueOp<R> Op;
-    Op x, y;
-    auto bind = [&](Op &op, uint32_t entry) {
-        Where wh;
-        wh.t = nullptr;
-        wh.tensor = 0;
-        wh.slot = entry;
-        wh.base = (uint64_t)entry * kChunk;
-        const uint64_t rem = a.numel - wh.base;
-        wh.len = rem < kChunk ? (uint32_t)rem : kChunk;
-        op.init(a, wh.base);
-        return wh;
-    };
-    ordered_stream<BLOCK, 2>(x, y, bind, nfull, nchunks, span, q);
-    leave_queue<false>(false, q, nullptr);
 }
 
 // Unfused pipeline: reduce the R partial outputs into an fp32 buffer (a lane owns 4 elements, so that the fp32

@@ -21,10 +21,7 @@ constexpr int32_t kMaxChunkElems = 1 << 24;      // lane offsets inside a chunk 
 constexpr int kBigBlock = 512, kSmallBlock = 128;
 constexpr int kOrderedMaxF32Slices = 4;           // fp32 slices: measured faster up to 4, slower at 8 (two chunks of 8 take 209 VGPRs)
 constexpr int64_t kOrderedMinChunksPerCu = 8;    // below this many chunks per compute unit a plan keeps one workgroup per chunk
-// A step whose buffers (R gradient slices, two copies of w, m, v and of the fp16 weights) stay below this many bytes
-// runs with plain instead of non-temporal accesses: it then lives in the 256 MB Infinity Cache from one step to the
-// next (size sweep: faster up to 2^22 elements at R = 8, slower from 2^23 on).
-constexpr uint64_t kResidentMaxBytes = 192u << 20;
+
 
 // Records the message for cc_last_error() on this thread and returns the code.
 int fail(cc_status code, const char *fmt, ...);

@@ -116,6 +116,18 @@ def test_workload_sizes():
     assert c2.wd_of(c2.params[0]) == 0.01 and c2.wd_of(c2.params[4]) == 0.0     # embedding decays, LayerNorm beta does not
 
 
+def test_only_the_c_abi_is_exported():
+    """The dynamic symbol table holds the declared entry points and nothing else (no kernel handles, no C++ helpers)."""
+    import shutil
+    import subprocess
+    nm = shutil.which("nm")
+    if nm is None:
+        pytest.skip("nm is not installed")
+    out = subprocess.check_output([nm, "-D", "--defined-only", cc.LIB_PATH], text=True)
+    names = {line.split()[-1] for line in out.splitlines() if line.strip()}
+    assert names == set(cc.EXPORTS), sorted(names ^ set(cc.EXPORTS))
+
+
 def _tensor(**kw):
     base = dict(numel=4096, w_in=0x1000, m_in=0x10000, v_in=0x20000, w_out=0x30000, m_out=0x40000, v_out=0x50000,
                 w16_out=0x60000, grad=[0x70000, 0x80000], weight_decay=0.0)

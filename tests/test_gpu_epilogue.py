@@ -108,36 +108,6 @@ def test_epilogue_at_the_paper_size_sampled():
     assert torch.equal(piece.view(torch.int16), out[a:b].view(torch.int16))
 
 
-@pytest.mark.parametrize("R", [2, 8])
-def test_ordered_epilogue_with_a_workspace_equals_the_plain_grid(R):
-    """A slice of 4 Mi elements and more with a workspace runs under the ordered persistent schedule: same bits as the
-    plain grid, the oracle on ranges that include chunk borders and the ragged end, the workspace left zero; twice in
-    a row, the second time on a shorter slice, so that a queue left dirty would show."""
-    H, p, seed = 1024, float(np.float32(0.1)), 77
-    ws = torch.zeros(64, dtype=torch.int32, device="cuda")
-    assert ws.data_ptr() % 256 == 0
-    for n, first in (((4 << 20) + 8192 * 3 + 24, 1024 * 9), ((4 << 20) + 8, 0)):
-        partials, bias, residual = make(n, R, H, 40 + R, scale=0.3)
-        a = torch.zeros(n, dtype=torch.float16, device="cuda")
-        b = torch.zeros(n, dtype=torch.float16, device="cuda")
-        cc.cc_fused_epilogue(partials, bias, residual, a, first, H, p, seed, workspace=ws)
-        cc.cc_fused_epilogue(partials, bias, residual, b, first, H, p, seed)
-        torch.cuda.synchronize()
-        assert not ws.any().item()
-        assert torch.equal(a.view(torch.int16), b.view(torch.int16))
-        bits = to_np_bits(a)
-        for lo in (0, 8192 * 255 - 100, n - 30000):
-            check(bits, partials, bias, residual, first, p, seed, lo, min(n, lo + 30000))
-    small = make(8192 * 4, R, H, 3)
-    out = torch.zeros(8192 * 4, dtype=torch.float16, device="cuda")
-    cc.cc_fused_epilogue(small[0], small[1], small[2], out, 0, H, p, seed, workspace=ws)      # below the size: the plain grid
-    with pytest.raises(cc.CcError) as e:
-        cc.cc_fused_epilogue(small[0], small[1], small[2], out, 0, H, p, seed, workspace=ws.data_ptr() + 16)
-    assert e.value.code == cc.CC_ERR_ALIGN
-    torch.cuda.synchronize()
-    check(to_np_bits(out), small[0], small[1], small[2], 0, p, seed)
-
-
 def test_epilogue_argument_checks():
     partials, bias, residual = make(64, 2, 8, 1)
     out = torch.zeros(64, dtype=torch.float16, device="cuda")

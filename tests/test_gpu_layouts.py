@@ -80,10 +80,9 @@ def test_single_tensor_plan_resident_and_streaming():
 
 def test_auto_policy_and_layout_rules():
     small = Shard([1 << 20], [0.0], 4, align_elems=8)
-    assert cc.cc_plan_layout(small.plans[0]) == (1024, 128, cc.CC_CACHE_RESIDENT)      # 35.7 MB of buffers: stays on chip
-    cc.cc_plan_set_cache_policy(small.plans[0], cc.CC_CACHE_STREAMING)
-    assert cc.cc_plan_layout(small.plans[0])[2] == cc.CC_CACHE_STREAMING
-    cc.cc_plan_set_cache_policy(small.plans[0], cc.CC_CACHE_AUTO)
+    assert cc.cc_plan_layout(small.plans[0]) == (1024, 128, cc.CC_CACHE_STREAMING)
+    cc.cc_plan_set_cache_policy(small.plans[0], cc.CC_CACHE_RESIDENT)
+    assert cc.cc_plan_layout(small.plans[0])[2] == cc.CC_CACHE_RESIDENT
     cc.cc_plan_set_chunk_elems(small.plans[0], 4096)
     assert cc.cc_plan_layout(small.plans[0]) == (4096, 512, cc.CC_CACHE_STREAMING)     # resident exists for 128-thread workgroups only
     with pytest.raises(cc.CcError) as e:
@@ -92,7 +91,9 @@ def test_auto_policy_and_layout_rules():
     with pytest.raises(cc.CcError):
         cc.cc_plan_set_cache_policy(small.plans[0], 9)
     cc.cc_plan_set_chunk_elems(small.plans[0], 0)
-    assert cc.cc_plan_layout(small.plans[0])[0] == 1024
+    assert cc.cc_plan_layout(small.plans[0]) == (1024, 128, cc.CC_CACHE_RESIDENT)
+    cc.cc_plan_set_cache_policy(small.plans[0], cc.CC_CACHE_AUTO)
+    assert cc.cc_plan_layout(small.plans[0])[2] == cc.CC_CACHE_STREAMING
     small.destroy()
     fixed = Shard([1 << 16], [0.0], 2, chunk_elems=2048, align_elems=8)                 # a caller's own chunk size: that one only
     assert cc.cc_plan_layout(fixed.plans[0])[:2] == (2048, 128)
