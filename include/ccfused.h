@@ -166,8 +166,9 @@ int cc_plan_layout(const cc_plan *plan, int32_t *chunk_elems, int32_t *block_thr
  * Cache policy of the streaming kernels' accesses.  STREAMING marks every access non-temporal (right for shards
  * that do not fit on chip).  RESIDENT uses plain accesses, so that a shard whose whole step fits the 256 MB Infinity
  * Cache may find its inputs on chip in the next step; it exists for 128-thread workgroups (chunks below 4096 elements)
- * and is ignored otherwise.  Which of the two is faster on a cache-resident shard differed from machine to machine,
- * so AUTO (default) is STREAMING and cc_plan_autotune tries both.
+ * and is ignored otherwise.  AUTO (default) picks RESIDENT when the step's buffers total between 64 and 200 MiB (too
+ * much for the L2s, little enough for the Infinity Cache: 6-10 % faster in the size sweep) and STREAMING otherwise;
+ * below 64 MiB the two differ by less than their spread from machine to machine.  cc_plan_autotune tries both.
  */
 typedef enum cc_cache_policy { CC_CACHE_AUTO = 0, CC_CACHE_STREAMING = 1, CC_CACHE_RESIDENT = 2 } cc_cache_policy;
 int cc_plan_set_cache_policy(cc_plan *plan, int32_t policy);

@@ -123,10 +123,13 @@ void resolve_schedule(cc_plan *p)
     else if (p->schedule == CC_SCHEDULE_PER_CHUNK) p->ordered = false;
     else p->ordered = L.chunks >= kOrderedMinChunksPerCu * (int64_t)p->cus && !(p->grad_f32 && p->R > kOrderedMaxF32Slices);
     if (L.chunk_elems != kDefaultChunkElems || L.chunks == 0) p->ordered = false;
-    // AUTO keeps the non-temporal hints: on cache-resident shards plain accesses were faster on some machines of the
-    // pool and slower on others (2^20 elements, R = 4: 5.1 against 5.4 us on one, 6.6 against 6.0 us on another), so
-    // the choice is left to the caller and to cc_plan_autotune
-    p->resident = p->cache_policy == CC_CACHE_RESIDENT && L.block == kSmallBlock && !p->ordered;
+    if (p->cache_policy == CC_CACHE_RESIDENT) p->resident = true;
+    else if (p->cache_policy == CC_CACHE_STREAMING) p->resident = false;
+    else {
+        const uint64_t footprint = p->numel * ((p->grad_f32 ? 4u : 2u) * (uint64_t)p->R + 12u + 14u);
+        p->resident = footprint >= kResidentMinBytes && footprint < kResidentMaxBytes;
+    }
+    if (L.block != kSmallBlock || p->ordered) p->resident = false;
 }
 
 void free_layout(Layout &L)

@@ -19,8 +19,13 @@ constexpr int32_t kLargeChunkElems = 16384;      // four sweeps of a 512-thread 
 constexpr uint64_t kSmallShardElems = 64u << 20; // below this many elements the default chunk is the small one (size sweep)
 constexpr int32_t kMaxChunkElems = 1 << 24;      // lane offsets inside a chunk are 32-bit byte offsets
 constexpr int kBigBlock = 512, kSmallBlock = 128;
-constexpr int kOrderedMaxF32Slices = 4;           // fp32 slices: measured faster up to 4, slower at 8 (two chunks of 8 take 209 VGPRs)
+constexpr int kOrderedMaxF32Slices = 8;           // fp32 slices: the ordered schedule wins up to 8 (config-2 list: 3.18 against 3.41 ms), at 16 two chunks spill
 constexpr int64_t kOrderedMinChunksPerCu = 8;    // below this many chunks per compute unit a plan keeps one workgroup per chunk
+// AUTO cache policy: plain instead of non-temporal accesses when the step's buffers (R gradient slices, both copies of
+// w, m, v and of the fp16 weights) total between these bounds, i.e. no longer fit the L2s but fit the 256 MB Infinity
+// Cache.  Size sweep at R = 8: 14.6 against 16.1 us at 2^21 elements (88 MB), 27.7 against 29.4 us at 2^22 (176 MB),
+// but 66.9 against 59.5 us at 2^23 (352 MB); below 64 MB the two differ by less than their spread from machine to machine.
+constexpr uint64_t kResidentMinBytes = 64ull << 20, kResidentMaxBytes = 200ull << 20;
 
 
 // Records the message for cc_last_error() on this thread and returns the code.

@@ -95,6 +95,9 @@ def test_auto_policy_and_layout_rules():
     cc.cc_plan_set_cache_policy(small.plans[0], cc.CC_CACHE_AUTO)
     assert cc.cc_plan_layout(small.plans[0])[2] == cc.CC_CACHE_STREAMING
     small.destroy()
+    mid = Shard([1 << 21], [0.0], 8, align_elems=8, unfused=False)                      # 88 MB of buffers: Infinity Cache, not L2
+    assert cc.cc_plan_layout(mid.plans[0]) == (1024, 128, cc.CC_CACHE_RESIDENT)
+    mid.destroy()
     fixed = Shard([1 << 16], [0.0], 2, chunk_elems=2048, align_elems=8)                 # a caller's own chunk size: that one only
     assert cc.cc_plan_layout(fixed.plans[0])[:2] == (2048, 128)
     with pytest.raises(cc.CcError):
