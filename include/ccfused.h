@@ -205,6 +205,22 @@ int cc_plan_info(const cc_plan *plan, uint64_t *numel, int64_t *chunks, uint64_t
 int cc_fused_adam_step(cc_plan *plan, const cc_hparams *hp, int32_t *d_overflow_flag, void *hip_stream);
 
 /*
+ * For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses that
+ * forbid it): the fused Adam step of cc_fused_adam_step on ONE tensor with fp16 gradient slices, without a plan.
+ * The call allocates nothing on the host or the device and creates no plan: the descriptor travels in the kernel
+ * arguments, and the kernel's only scratch memory, the counting words of the overflow flag (16.6 KB), lives in a
+ * static device array of the library that every GPU the library runs on holds until the process ends.  Same kernel,
+ * same results bit for bit as cc_fused_adam_step on a single-tensor plan with 1024-element chunks.
+ * `tensor` is a host pointer to one cc_tensor (device buffers as for a plan, same alignment and overlap rules).
+ * numel may be 0 (the flag is cleared) and at most 2^26 (64 Mi) elements: larger tensors are rejected with CC_ERR_ARG,
+ * they belong to a plan and the ordered schedule.  All calls on one GPU share that GPU's array, which keeps its
+ * contents from call to call (the counting words leave every launch in the state the next one expects, whatever
+ * the two sizes); calls that overlap in time on one GPU race on it, so they must be ordered (one stream, or events).
+ */
+int cc_fused_adam_step_static(const cc_tensor *tensor, int32_t R, const cc_hparams *hp, int32_t *d_overflow_flag,
+                              void *hip_stream);
+
+/*
  * LAMB, two sweeps around a per-tensor reduction (Section 5.2 "Tensor Reduction": each rank reduces
  * locally).  Phase 1 reduces the gradients, writes m', v' and accumulates sum(w^2), sum(u^2) per tensor
  * (u as above, w before the update).  Phase 2 forms ratio = ||w||/||u|| (1 if either norm is 0) and

@@ -69,6 +69,7 @@ EXPORTS = {
                                    C.POINTER(C.c_float), C.POINTER(C.c_float)]),
     "cc_plan_info": (C.c_int, [C.c_void_p, C.POINTER(C.c_uint64), C.POINTER(C.c_int64), C.POINTER(C.c_uint64)]),
     "cc_fused_adam_step": (C.c_int, [C.c_void_p, C.POINTER(cc_hparams), C.c_void_p, C.c_void_p]),
+    "cc_fused_adam_step_static": (C.c_int, [C.POINTER(cc_tensor), C.c_int32, C.POINTER(cc_hparams), C.c_void_p, C.c_void_p]),
     "cc_fused_lamb_step": (C.c_int, [C.c_void_p, C.POINTER(cc_hparams), C.c_void_p, C.c_void_p]),
     "cc_fused_lamb_phase1": (C.c_int, [C.c_void_p, C.POINTER(cc_hparams), C.c_void_p, C.c_void_p]),
     "cc_fused_lamb_phase2": (C.c_int, [C.c_void_p, C.POINTER(cc_hparams), C.c_void_p, C.c_void_p]),
@@ -291,6 +292,11 @@ def _step(name: str, plan: Plan, hp, flag, stream) -> None:
 
 def cc_fused_adam_step(plan: Plan, hp, flag, stream=None) -> None:
     _step("cc_fused_adam_step", plan, hp, flag, stream)
+
+
+def cc_fused_adam_step_static(tensor: Tensor, R: int, hp, flag, stream=None) -> None:
+    t, c = _c_tensor(tensor), _hp(hp)
+    _check(load().cc_fused_adam_step_static(C.byref(t), R, C.byref(c), _ptr(flag), _stream(stream)))
 
 
 def cc_fused_lamb_step(plan: Plan, hp, flag, stream=None) -> None:

@@ -7,6 +7,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -488,9 +489,8 @@ namespace {
 
 enum class Opt { Adam, Lamb };
 
-int check_step(const cc_plan *p, const cc_hparams *hp, const void *flag, Opt opt, StepScalars *s)
+int check_hparams(const cc_hparams *hp, const void *flag, Opt opt, int32_t R, bool in_place, int32_t chunk_elems, StepScalars *s)
 {
-    if (!p) return fail(CC_ERR_NULL, "plan is NULL");
     if (!hp) return fail(CC_ERR_NULL, "hparams is NULL");
     if (!flag) return fail(CC_ERR_NULL, "d_overflow_flag is NULL");
     if (hp->step < 1) return fail(CC_ERR_ARG, "step = %d must be >= 1", hp->step);
@@ -504,7 +504,7 @@ int check_step(const cc_plan *p, const cc_hparams *hp, const void *flag, Opt opt
     if (hp->skip_mode != 0 && hp->skip_mode != 1) return fail(CC_ERR_ARG, "skip_mode = %d", hp->skip_mode);
     if (opt == Opt::Lamb && (hp->adam_mode != 1 || hp->skip_mode != 0))
         return fail(CC_ERR_ARG, "LAMB supports adam_mode = 1 and skip_mode = 0 only");
-    if (hp->skip_mode == 0 && p->in_place)
+    if (hp->skip_mode == 0 && in_place)
         return fail(CC_ERR_ALIAS, "skip_mode 0 (whole-step skip) needs out buffers distinct from the in buffers");
     const double b1 = hp->beta1, b2 = hp->beta2;
     const double c1 = 1.0 - std::pow(b1, (double)hp->step), c2 = 1.0 - std::pow(b2, (double)hp->step);
@@ -516,9 +516,15 @@ int check_step(const cc_plan *p, const cc_hparams *hp, const void *flag, Opt opt
     s->rc2 = (float)(1.0 / c2);
     s->eps = hp->eps;
     s->lr = hp->lr;
-    s->inv_div = (float)(1.0 / ((double)hp->loss_scale * (hp->grad_average ? (double)p->R : 1.0)));
-    s->chunk_elems = (uint32_t)p->lay().chunk_elems;
+    s->inv_div = (float)(1.0 / ((double)hp->loss_scale * (hp->grad_average ? (double)R : 1.0)));
+    s->chunk_elems = (uint32_t)chunk_elems;
     return CC_OK;
+}
+
+int check_step(const cc_plan *p, const cc_hparams *hp, const void *flag, Opt opt, StepScalars *s)
+{
+    if (!p) return fail(CC_ERR_NULL, "plan is NULL");
+    return check_hparams(hp, flag, opt, p->R, p->in_place, p->lay().chunk_elems, s);
 }
 
 // The unfused pipelines need the plan's fp32 reduced-gradient buffer; a step call does not allocate it.
@@ -543,6 +549,104 @@ int cc_fused_adam_step(cc_plan *p, const cc_hparams *hp, int32_t *flag, void *st
     if (p->grad_f32) launch_fused_adam_f32(p, s, flag, st, mode);
     else launch_fused_adam_f16(p, s, flag, st, mode);
     return launched("fused_adam_kernel");
+}
+
+}  // extern "C"
+
+// ---- a fused Adam step that allocates nothing ------------------------------------------------------------------------
+// The only memory the small-shard kernel needs beyond the caller's buffers are the counting words of the overflow
+// flag (FlagScratch).  For callers that cannot allocate they live in this array, one copy per device, for as long as
+// the process runs.  In host code the array's name is only a handle: the device address comes from
+// hipGetSymbolAddress, once per device, and that pointer is what the kernels receive.
+static __device__ __align__(256) unsigned char scratch[sizeof(ccf::FlagScratch)];
+
+namespace {
+
+constexpr uint64_t kStaticMaxElems = 64ull << 20;        // 65536 workgroups of 1024 elements
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mutex;
+ccf::FlagScratch *g_static_scratch[kMaxDevices] = {};
+
+// The device address of this device's copy of `scratch` (looked up on the first call on each device).
+int static_scratch(ccf::FlagScratch **out)
+{
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(CC_ERR_ARG, "device %d is outside 0..%d", dev, kMaxDevices - 1);
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    if (!g_static_scratch[dev]) {
+        void *ptr = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) return fail(CC_ERR_HIP, "hipGetSymbolAddress returned no address for the scratch array");
+        g_static_scratch[dev] = (ccf::FlagScratch *)ptr;
+    }
+    *out = g_static_scratch[dev];
+    return CC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int cc_fused_adam_step_static(const cc_tensor *t, int32_t R, const cc_hparams *hp, int32_t *flag, void *stream)
+{
+    if (!t) return fail(CC_ERR_NULL, "cc_fused_adam_step_static: tensor is NULL");
+    if (R < 1 || R > CC_MAX_R) return fail(CC_ERR_ARG, "cc_fused_adam_step_static: R = %d outside 1..%d", R, CC_MAX_R);
+    if (t->numel > kStaticMaxElems)
+        return fail(CC_ERR_ARG, "cc_fused_adam_step_static: numel = %llu exceeds the maximum of %llu elements; use a plan",
+                    (unsigned long long)t->numel, (unsigned long long)kStaticMaxElems);
+    bool in_place = false;
+    if (t->numel > 0) {
+        if (!std::isfinite(t->weight_decay)) return fail(CC_ERR_ARG, "weight_decay is not finite");
+        const void *ptrs[7] = {t->w_in, t->m_in, t->v_in, t->w_out, t->m_out, t->v_out, t->w16_out};
+        static const char *names[7] = {"w_in", "m_in", "v_in", "w_out", "m_out", "v_out", "w16_out"};
+        for (int k = 0; k < 7; ++k) {
+            if (!ptrs[k]) return fail(CC_ERR_NULL, "%s is NULL", names[k]);
+            if (misaligned(ptrs[k])) return fail(CC_ERR_ALIGN, "%s is not 16-byte aligned", names[k]);
+        }
+        for (int r = 0; r < R; ++r) {
+            if (!t->grad[r]) return fail(CC_ERR_NULL, "grad[%d] is NULL", r);
+            if (misaligned(t->grad[r])) return fail(CC_ERR_ALIGN, "grad[%d] is not 16-byte aligned", r);
+        }
+        // the same overlap rule as a plan's, on this one tensor's buffers (a fixed array: nothing is allocated)
+        struct Buf { uintptr_t begin, end; bool output; } bufs[7 + CC_MAX_R];
+        int n = 0;
+        for (int k = 0; k < 3; ++k) {
+            const uintptr_t i = reinterpret_cast<uintptr_t>(ptrs[k]), o = reinterpret_cast<uintptr_t>(ptrs[3 + k]);
+            bufs[n++] = Buf{o, o + t->numel * 4, true};
+            if (i == o) in_place = true;
+            else bufs[n++] = Buf{i, i + t->numel * 4, false};
+        }
+        const uintptr_t h = reinterpret_cast<uintptr_t>(t->w16_out);
+        bufs[n++] = Buf{h, h + t->numel * 2, true};
+        for (int r = 0; r < R; ++r) {
+            const uintptr_t g = reinterpret_cast<uintptr_t>(t->grad[r]);
+            bufs[n++] = Buf{g, g + t->numel * 2, false};
+        }
+        for (int a = 0; a < n; ++a)
+            for (int b = a + 1; b < n; ++b)
+                if ((bufs[a].output || bufs[b].output) && bufs[a].begin < bufs[b].end && bufs[b].begin < bufs[a].end)
+                    return fail(CC_ERR_ALIAS, "two of the tensor's buffers overlap and one of them is an output");
+    }
+    StepScalars s;
+    int rc = check_hparams(hp, flag, Opt::Adam, R, in_place, kSmallChunkElems, &s);
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    if (t->numel == 0) return clear_flag(flag, st);
+    FlagScratch *fs = nullptr;
+    if ((rc = static_scratch(&fs))) return rc;
+    DevTensor d;
+    std::memset(&d, 0, sizeof(d));
+    d.numel = t->numel;
+    d.w_in = t->w_in; d.m_in = t->m_in; d.v_in = t->v_in;
+    d.w_out = t->w_out; d.m_out = t->m_out; d.v_out = t->v_out;
+    d.w16 = t->w16_out;
+    for (int r = 0; r < R; ++r) d.grad[r] = t->grad[r];
+    d.wd = t->weight_decay;
+    const unsigned grid = (unsigned)((t->numel + (uint64_t)kSmallChunkElems - 1) / (uint64_t)kSmallChunkElems);
+    const int mode = (hp->skip_mode == 1 ? kModeGuard : 0) | (hp->adam_mode == 0 ? kModeL2 : 0);
+    launch_fused_adam_flat_f16(d, R, grid, false, s, fs, flag, st, mode);
+    return launched("fused_adam_flat_kernel");
 }
 
 int cc_fused_lamb_phase1(cc_plan *p, const cc_hparams *hp, int32_t *flag, void *stream)

@@ -227,6 +227,27 @@ def test_step_calls_reject_null_plan_and_bad_copy_arguments():
     assert "multiple of 1024" in cc.cc_last_error()
 
 
+def test_static_step_rejects_bad_arguments_on_the_host():
+    """The checks of the entry point that allocates nothing run before any device call."""
+    lib = cc.load()
+    hp = cc.Hyper().to_c()
+    assert lib.cc_fused_adam_step_static(None, 2, C.byref(hp), 0x1000, None) == cc.CC_ERR_NULL
+
+    def call(t, R=2, h=hp, flag=0x1000):
+        c = cc._c_tensor(t)
+        return lib.cc_fused_adam_step_static(C.byref(c), R, C.byref(h) if h is not None else None, flag, None)
+    assert call(_tensor(), R=0) == cc.CC_ERR_ARG and call(_tensor(), R=17) == cc.CC_ERR_ARG
+    assert call(_tensor(numel=(1 << 26) + 1)) == cc.CC_ERR_ARG and "maximum" in cc.cc_last_error()
+    assert call(_tensor(w_in=0)) == cc.CC_ERR_NULL
+    assert call(_tensor(grad=[0x70000, 0x80008])) == cc.CC_ERR_ALIGN
+    assert call(_tensor(w16_out=0x30000 + 0x1000)) == cc.CC_ERR_ALIAS
+    assert call(_tensor(grad=[0x40000 + 0x100, 0x80000])) == cc.CC_ERR_ALIAS
+    assert call(_tensor(w_in=0x30000)) == cc.CC_ERR_ALIAS                       # in place needs skip_mode 1
+    assert call(_tensor(), h=None) == cc.CC_ERR_NULL
+    assert call(_tensor(), flag=None) == cc.CC_ERR_NULL
+    assert call(_tensor(), h=cc.Hyper(step=0).to_c()) == cc.CC_ERR_ARG
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(cc, "_lib", None)
     monkeypatch.setattr(cc, "LIB_PATH", str(tmp_path / "absent.so"))
