@@ -85,3 +85,61 @@ def test_static_entry_point_rejects_what_it_cannot_do():
     torch.cuda.synchronize()
     assert int(sh.flag.item()) == 0
     sh.destroy()
+
+
+def test_static_entry_point_flag_over_many_launches_of_random_size():
+    """The counting words are shared by every call on the GPU and are never reset from outside: 300 launches of random
+    size, a third of them with an inf or NaN planted at a random place (first element, last element, anywhere, in any
+    slice), must each report exactly their own flag, whatever ran before."""
+    import random
+    rng = random.Random(7)
+    R, nmax = 3, 1 << 19
+    sh = Shard([nmax], [0.0], R, chunk_elems=1024, align_elems=8)
+    seeded_state(sh, 1)
+    seeded_grads(sh, 10, 1e-2)
+    clean = [g.clone() for g in sh.grads]
+    wrong = []
+    for i in range(300):
+        n = rng.choice((1, 63, 64, 1023, 1024, 1025, 4096, 65 * 1024, 127 * 1024, 128 * 1024 + 1, rng.randrange(1, nmax + 1)))
+        want = 0
+        if rng.random() < 0.33:
+            r, where = rng.randrange(R), rng.choice((0, n - 1, rng.randrange(n)))
+            sh.grads[r].view(torch.int16)[where] = rng.choice((0x7C00, -1024, 0x7E00))      # +inf, -inf (0xFC00), NaN
+            want = 1
+        t = cc.Tensor(numel=n, w_in=sh.w[0], m_in=sh.m[0], v_in=sh.v[0], w_out=sh.w[1], m_out=sh.m[1], v_out=sh.v[1],
+                      w16_out=sh.w16[1], grad=list(sh.grads), weight_decay=0.0)
+        cc.cc_fused_adam_step_static(t, R, cc.Hyper(step=1), sh.flag)
+        got = int(sh.flag.item())
+        if got != want:
+            wrong.append((i, n, want, got))
+        if want:
+            for g, c in zip(sh.grads, clean):
+                g.copy_(c)
+    assert not wrong, wrong[:10]
+    sh.destroy()
+
+
+def test_static_entry_point_under_graph_capture():
+    """It allocates nothing, so the very first call may already sit inside a capture; every replay gives the eager result."""
+    n, R = 200000, 4
+    a = Shard([n], [0.01], R, chunk_elems=1024, align_elems=8)
+    b = Shard([n], [0.01], R, chunk_elems=1024, align_elems=8)
+    for sh in (a, b):
+        seeded_state(sh, 9)
+        seeded_grads(sh, 90, 1e-2)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        cc.cc_fused_adam_step_static(one_tensor_of(b, 0), R, cc.Hyper(step=1), b.flag)
+    for rep in range(3):
+        if rep:
+            for sh in (a, b):
+                seeded_grads(sh, 90 + rep, 1e-2)
+                if rep == 2:
+                    sh.grads[1].view(torch.int16)[n - 1] = 0x7C00
+        a.run(cc.cc_fused_adam_step, cc.Hyper(step=1))
+        g.replay()
+        torch.cuda.synchronize()
+        assert int(a.flag.item()) == int(b.flag.item()) == (1 if rep == 2 else 0)
+        for x, y in zip(bits(a, 1), bits(b, 1)):
+            assert torch.equal(x, y)
+    a.destroy(); b.destroy()
