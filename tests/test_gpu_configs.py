@@ -9,7 +9,6 @@ unfused pipeline over all elements.
 """
 import math
 
-import numpy as np
 import pytest
 import torch
 
@@ -17,8 +16,7 @@ import oracle
 from paper_2105_05720_amd import binding as cc
 from paper_2105_05720_amd import workloads as W
 from paper_2105_05720_amd.shard import Shard
-from parity import FullOracle, OracleState, all_inputs_finite, hyper_pair, run_steps, to_np_bits, to_np_f32, grad_to_np, THREADS
-from util import half_ulp_distance, state_error
+from parity import FullOracle, OracleState, all_inputs_finite, hyper_pair, run_steps
 
 pytestmark = pytest.mark.gpu
 
@@ -143,51 +141,20 @@ def test_config4_adam_gpt2_xl_overflow_skip_every_element():
     shard.destroy()
 
 
-class SampledOracle:
-    """Oracle state for a strided sample of every tensor's elements (valid for element-independent Adam)."""
-
-    def __init__(self, shard, cfg, stride):
-        self.idx = []
-        for s in cfg.params:
-            n = s.numel
-            ix = torch.arange(0, n, stride, device=shard.device)
-            tail = torch.arange(max(0, n - 9), n, device=shard.device)
-            self.idx.append(torch.unique(torch.cat([ix, tail])))
-        self.w = [to_np_f32(shard.w_of(k)[ix]) for k, ix in enumerate(self.idx)]
-        self.m = [to_np_f32(shard.m_of(k)[ix]) for k, ix in enumerate(self.idx)]
-        self.v = [to_np_f32(shard.v_of(k)[ix]) for k, ix in enumerate(self.idx)]
-        self.count = sum(int(ix.numel()) for ix in self.idx)
-
-    def step(self, shard, cfg, ohp):
-        ots = [oracle.OracleTensor(w=self.w[k], m=self.m[k], v=self.v[k],
-                                   grads=[grad_to_np(shard, shard.grad_of(r, k)[ix]) for r in range(cfg.R)],
-                                   weight_decay=shard.wds[k]) for k, ix in enumerate(self.idx)]
-        flag = oracle.adam_step(ots, ohp, threads=THREADS)
-        self.w = [t.w_out for t in ots]
-        self.m = [t.m_out for t in ots]
-        self.v = [t.v_out for t in ots]
-        self.w16 = [t.w16_out for t in ots]
-        return flag
-
-    def compare(self, shard, label):
-        for k, ix in enumerate(self.idx):
-            for name, got, want in (("w", shard.w_of(k), self.w[k]), ("m", shard.m_of(k), self.m[k]), ("v", shard.v_of(k), self.v[k])):
-                ratio, rel, cnt = state_error(to_np_f32(got[ix]), want)
-                assert ratio <= 1.0, "%s: tensor %d %s off by %.3g x the bound (max rel %.3g)" % (label, k, name, ratio, rel)
-            d = half_ulp_distance(to_np_bits(shard.w16_of(k)[ix]), self.w16[k])
-            assert d.size == 0 or d.max() <= 1, "%s: tensor %d fp16 weights differ by %d ulp" % (label, k, d.max())
-
-
-def test_config2_list_with_fp32_gradient_slices_sampled():
-    """The Float 32 variant of the workload (paper, Section 6.1.1): same list, the R slices kept in fp32."""
+def test_config2_list_with_fp32_gradient_slices_every_element():
+    """The Float 32 variant of the workload (paper, Section 6.1.1): same list, the R slices kept in fp32, under the
+    schedule AUTO picks for it (ordered), two steps, every element."""
     cfg = W.config(2)
     shard = shard_for(cfg, grad_dtype=torch.float32)
-    samp = SampledOracle(shard, cfg, stride=97)
+    assert cc.cc_plan_schedule(shard.plans[0])[0] == cc.CC_SCHEDULE_ORDERED
+    full = FullOracle(shard)
     for t in (1, 2):
         ghp, ohp = hp_of(cfg, t)
         W.fill_grads(shard, cfg, t)
-        assert samp.step(shard, cfg, ohp) == 0
+        torch.cuda.synchronize()
+        assert full.step(shard, ohp, "adam") == 0
         assert shard.step(cc.cc_fused_adam_step, ghp) == 0
         torch.cuda.synchronize()
-        samp.compare(shard, "config 2 fp32 slices step %d" % t)
+        worst = full.compare(shard, "config 2 fp32 slices step %d" % t)
+        print("config 2 with fp32 slices step %d: %d of %d elements checked, worst %.3f x the bound" % (t, full.elements, cfg.numel, worst), flush=True)
     shard.destroy()

@@ -131,3 +131,16 @@ def test_unfused_steps_need_the_reserved_buffer_and_never_allocate():
     sh.commit(); ref.commit()
     assert all(torch.equal(a, b) for a, b in zip(bits_of(sh), bits_of(ref)))
     sh.destroy(); ref.destroy()
+
+
+@pytest.mark.parametrize("fn,ofn", [(cc.cc_fused_adam_step, oracle.adam_step), (cc.cc_fused_lamb_step, oracle.lamb_step)])
+def test_mid_size_shard_under_the_automatic_cache_policy(fn, ofn):
+    """2^21 elements with R = 8: 88 MB of buffers, where AUTO drops the non-temporal hints; two steps, every element."""
+    n = 1 << 21
+    sh = Shard([n - 4096 * 100 - 3, 4096 * 100 + 3], [0.01, 0.0], 8, unfused=False)
+    assert cc.cc_plan_layout(sh.plans[0]) == (1024, 128, cc.CC_CACHE_RESIDENT)
+    seeded_state(sh, 8)
+    ost = OracleState(sh, [0, 1])
+    run_steps(sh, ost, fn, ofn, [hyper_pair(step=t) for t in (1, 2)], "2^21 resident", lambda i: seeded_grads(sh, 800 + i, 1e-3),
+              expect_flags=[0, 0])
+    sh.destroy()
