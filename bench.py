@@ -139,7 +139,8 @@ def describe(cc, shard, R, optimizer, gf32):
     return {"chunk_elems": chunk, "chunks": chunks, "table_bytes": table_bytes, "kernel": kernel,
             "schedule": ("ordered: %d persistent workgroups take the chunks in table order" % wgs) if ordered
             else "one workgroup of %d threads per chunk" % block,
-            "cache_policy": "plain accesses (cache-resident shard)" if policy == cc.CC_CACHE_RESIDENT else "non-temporal accesses"}
+            "cache_policy": {cc.CC_CACHE_RESIDENT: "plain loads, write-through stores (cache-resident shard)",
+                             cc.CC_CACHE_WRITE_THROUGH: "non-temporal loads, write-through stores"}.get(policy, "non-temporal accesses")}
 
 
 def main() -> int:
@@ -158,7 +159,7 @@ def main() -> int:
     ap.add_argument("--schedule", choices=("auto", "per-chunk", "ordered", "tuned"), default="auto",
                     help="how the kernels are laid over the device (cc_plan_set_schedule); auto = the library's size rule, "
                          "tuned = cc_plan_autotune measures the candidates on this workload first")
-    ap.add_argument("--cache", choices=("auto", "streaming", "resident"), default="auto", help="cc_plan_set_cache_policy")
+    ap.add_argument("--cache", choices=("auto", "streaming", "resident", "write-through"), default="auto", help="cc_plan_set_cache_policy")
     ap.add_argument("--workgroups", type=int, default=0, help="workgroups of the ordered schedule (0 = one per compute unit)")
     ap.add_argument("--no-extras", action="store_true", help="only the headline step (for profiling runs)")
     ap.add_argument("--copy-only", action="store_true", help="run only the plain copy kernel (2 GiB, 20 launches): counter calibration")
@@ -201,7 +202,8 @@ def main() -> int:
     K, Wm = args.steps, args.warmup
     sched_arg = {"auto": cc.CC_SCHEDULE_AUTO, "per-chunk": cc.CC_SCHEDULE_PER_CHUNK, "ordered": cc.CC_SCHEDULE_ORDERED,
                  "tuned": cc.CC_SCHEDULE_AUTO}[args.schedule]
-    cache_arg = {"auto": cc.CC_CACHE_AUTO, "streaming": cc.CC_CACHE_STREAMING, "resident": cc.CC_CACHE_RESIDENT}[args.cache]
+    cache_arg = {"auto": cc.CC_CACHE_AUTO, "streaming": cc.CC_CACHE_STREAMING, "resident": cc.CC_CACHE_RESIDENT,
+                 "write-through": cc.CC_CACHE_WRITE_THROUGH}[args.cache]
     default_options = (args.chunk_elems == 0 and not args.in_place and not args.flat and args.grad_dtype == "f16"
                        and args.schedule == "auto" and args.workgroups == 0 and args.cache == "auto")
 

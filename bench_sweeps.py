@@ -21,9 +21,9 @@ from paper_2105_05720_amd import binding as cc
 from paper_2105_05720_amd.shard import Shard
 
 PC, ORD = cc.CC_SCHEDULE_PER_CHUNK, cc.CC_SCHEDULE_ORDERED
-STREAM, RESIDENT = cc.CC_CACHE_STREAMING, cc.CC_CACHE_RESIDENT
+STREAM, RESIDENT, THROUGH = cc.CC_CACHE_STREAMING, cc.CC_CACHE_RESIDENT, cc.CC_CACHE_WRITE_THROUGH
 # (chunk elements, schedule, cache policy, label): what cc_plan_autotune chooses among
-SHAPES = ((1024, PC, RESIDENT, "1024 resident"), (1024, PC, STREAM, "1024"), (4096, PC, STREAM, "4096"),
+SHAPES = ((1024, PC, RESIDENT, "1024 resident"), (1024, PC, THROUGH, "1024 write-through"), (1024, PC, STREAM, "1024"), (4096, PC, STREAM, "4096"),
           (16384, PC, STREAM, "16384"), (4096, ORD, STREAM, "4096 ordered"))
 
 
@@ -226,6 +226,10 @@ def mode_epilogue(argv) -> int:
     return 0
 
 
+POLICIES = ((STREAM, "non-temporal loads and stores"), (RESIDENT, "plain loads, write-through stores"),
+            (THROUGH, "non-temporal loads, write-through stores"))
+
+
 def mode_small(argv) -> int:
     ap = argparse.ArgumentParser(prog="bench.py --mode small")
     ap.add_argument("--log2", type=int, default=20)
@@ -245,8 +249,9 @@ def mode_small(argv) -> int:
     rows = []
     names = {0: "empty workgroups", 1: "loads only", 2: "stores only", 3: "loads + stores, no arithmetic, no flag"}
     variants = [(names[what], pname, (lambda i, what=what, policy=policy: cc.cc_pattern_probe(tensors[i & 1], R, what, policy, sink)))
-                for what in (0, 1, 2, 3) for policy, pname in ((STREAM, "non-temporal"), (RESIDENT, "plain")) if not (what == 0 and policy == RESIDENT)]
-    for policy, pname in ((STREAM, "non-temporal"), (RESIDENT, "plain")):
+                for what in (0, 1, 2, 3) for policy, pname in POLICIES
+                if policy == STREAM or what == 3 or (what, policy) in ((1, RESIDENT), (2, THROUGH))]
+    for policy, pname in POLICIES:
         def full(i, policy=policy):
             shard.run(cc.cc_fused_adam_step, cc.Hyper(step=1 + i))
             shard.commit()

@@ -157,27 +157,28 @@ int cc_plan_schedule(const cc_plan *plan, int32_t *schedule, int32_t *workgroups
  * Chunk size of the step calls: one of the sizes the plan was prepared for (see cc_plan_create), or 0 for the size
  * rule.  Adam results do not depend on it; LAMB's norms are summed chunk by chunk, so they move in the last bits.
  * cc_plan_layout reports what the plan will use (each pointer may be NULL): chunk size, threads per workgroup,
- * cache policy (CC_CACHE_STREAMING or CC_CACHE_RESIDENT).
+ * cache policy (CC_CACHE_STREAMING, CC_CACHE_RESIDENT or CC_CACHE_WRITE_THROUGH).
  */
 int cc_plan_set_chunk_elems(cc_plan *plan, int32_t chunk_elems);
 int cc_plan_layout(const cc_plan *plan, int32_t *chunk_elems, int32_t *block_threads, int32_t *cache_policy);
 
 /*
- * Cache policy of the streaming kernels' accesses.  STREAMING marks every access non-temporal (right for shards
- * that do not fit on chip).  RESIDENT uses plain accesses, so that a shard whose whole step fits the 256 MB Infinity
- * Cache may find its inputs on chip in the next step; it exists for 128-thread workgroups (chunks below 4096 elements)
- * and is ignored otherwise.  AUTO (default) picks RESIDENT when the step's buffers total between 64 and 200 MiB (too
- * much for the L2s, little enough for the Infinity Cache: 6-10 % faster in the size sweep) and STREAMING otherwise;
- * below 64 MiB the two differ by less than their spread from machine to machine.  cc_plan_autotune tries both.
+ * Cache policy of the streaming kernels' accesses.  STREAMING marks every access non-temporal (right for shards far
+ * beyond what the chip holds).  RESIDENT uses plain loads and write-through stores, so that a shard whose whole step
+ * fits the 256 MB Infinity Cache finds its inputs on chip in the next step.  WRITE_THROUGH keeps the non-temporal loads
+ * and writes the stores through, for shards of a few times that cache.  The last two exist for 128-thread workgroups
+ * (chunks below 4096 elements) and are ignored otherwise.  Results do not depend on the policy.  AUTO (default) goes by
+ * the bytes of the step's buffers: RESIDENT below 200 MiB (4-20 % faster than STREAMING between 2^18 and 2^22 elements
+ * in the size sweep, equal below), WRITE_THROUGH from there to 900 MiB (8-11 % faster at 2^23 and 2^24 elements), STREAMING beyond.  cc_plan_autotune tries all.
  */
-typedef enum cc_cache_policy { CC_CACHE_AUTO = 0, CC_CACHE_STREAMING = 1, CC_CACHE_RESIDENT = 2 } cc_cache_policy;
+typedef enum cc_cache_policy { CC_CACHE_AUTO = 0, CC_CACHE_STREAMING = 1, CC_CACHE_RESIDENT = 2, CC_CACHE_WRITE_THROUGH = 3 } cc_cache_policy;
 int cc_plan_set_cache_policy(cc_plan *plan, int32_t policy);
 
 /*
  * Picks chunk size, workgroup size, cache policy, schedule and workgroup count by measurement instead of by the size
  * rule, as the paper's autotuner keeps the fastest schedule per workload (Section 3.5): runs the plan's own fused
  * step (optimizer 0 = Adam, 1 = LAMB) a few times under each candidate (one workgroup per chunk for every chunk size
- * the plan was prepared for, with both cache policies where they exist; ordered with compute units / 2, x 1 and x 2
+ * the plan was prepared for, with every cache policy that exists for it; ordered with compute units / 2, x 1 and x 2
  * workgroups on the 4096-element chunks), timed with events on `hip_stream`, and leaves the plan set to the fastest.  The
  * trial steps are ordinary steps on the caller's buffers: they write the out buffers and the flag, never the in
  * buffers, so the plan must be out of place (CC_ERR_ALIAS otherwise) and the caller must not have adopted the out
@@ -303,7 +304,7 @@ int cc_copy_probe(void *d_dst, const void *d_src, uint64_t bytes, void *hip_stre
  * 1024, one 128-thread workgroup per 1024 elements) with parts taken away, to show where a launch-bound step's time
  * goes: what = 0 empty workgroups, 1 the loads only, 2 the stores only (w_out, m_out, v_out, w16_out receive filler
  * values), 3 loads and stores without the update arithmetic and without the flag (outputs are not an Adam step).
- * cache_policy: CC_CACHE_STREAMING or CC_CACHE_RESIDENT.  d_sink: one device int32 (never written in practice). */
+ * cache_policy: CC_CACHE_STREAMING, CC_CACHE_RESIDENT or CC_CACHE_WRITE_THROUGH.  d_sink: one device int32 (never written in practice). */
 int cc_pattern_probe(const cc_tensor *tensor, int32_t R, int32_t what, int32_t cache_policy, int32_t *d_sink,
                      void *hip_stream);
 

@@ -13,7 +13,7 @@ from typing import List, Optional, Sequence
 CC_MAX_R = 16
 CC_GRAD_F16, CC_GRAD_F32 = 0, 1
 CC_SCHEDULE_AUTO, CC_SCHEDULE_PER_CHUNK, CC_SCHEDULE_ORDERED = 0, 1, 2
-CC_CACHE_AUTO, CC_CACHE_STREAMING, CC_CACHE_RESIDENT = 0, 1, 2
+CC_CACHE_AUTO, CC_CACHE_STREAMING, CC_CACHE_RESIDENT, CC_CACHE_WRITE_THROUGH = 0, 1, 2, 3
 CC_OK, CC_ERR_NULL, CC_ERR_ARG, CC_ERR_ALIGN, CC_ERR_ALIAS, CC_ERR_HIP, CC_ERR_NOMEM = 0, -1, -2, -3, -4, -5, -6
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -247,7 +247,7 @@ def cc_plan_set_chunk_elems(plan: Plan, chunk_elems: int = 0) -> None:
 
 
 def cc_plan_layout(plan: Plan):
-    """(chunk size in elements, threads per workgroup, CC_CACHE_STREAMING or CC_CACHE_RESIDENT) the plan will use."""
+    """(chunk size in elements, threads per workgroup, CC_CACHE_STREAMING, CC_CACHE_RESIDENT or CC_CACHE_WRITE_THROUGH) the plan will use."""
     ce, blk, pol = C.c_int32(), C.c_int32(), C.c_int32()
     _check(load().cc_plan_layout(plan.handle, C.byref(ce), C.byref(blk), C.byref(pol)))
     return ce.value, blk.value, pol.value

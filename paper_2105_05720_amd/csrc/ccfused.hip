@@ -124,13 +124,9 @@ void resolve_schedule(cc_plan *p)
     else if (p->schedule == CC_SCHEDULE_PER_CHUNK) p->ordered = false;
     else p->ordered = L.chunks >= kOrderedMinChunksPerCu * (int64_t)p->cus && !(p->grad_f32 && p->R > kOrderedMaxF32Slices);
     if (L.chunk_elems != kDefaultChunkElems || L.chunks == 0) p->ordered = false;
-    if (p->cache_policy == CC_CACHE_RESIDENT) p->resident = true;
-    else if (p->cache_policy == CC_CACHE_STREAMING) p->resident = false;
-    else {
-        const uint64_t footprint = p->numel * ((p->grad_f32 ? 4u : 2u) * (uint64_t)p->R + 12u + 14u);
-        p->resident = footprint >= kResidentMinBytes && footprint < kResidentMaxBytes;
-    }
-    if (L.block != kSmallBlock || p->ordered) p->resident = false;
+    if (p->cache_policy != CC_CACHE_AUTO) p->mem = p->cache_policy;
+    else p->mem = auto_cache_policy(p->numel * ((p->grad_f32 ? 4u : 2u) * (uint64_t)p->R + 12u + 14u));
+    if (L.block != kSmallBlock || p->ordered) p->mem = CC_CACHE_STREAMING;
 }
 
 void free_layout(Layout &L)
@@ -395,14 +391,14 @@ int cc_plan_layout(const cc_plan *p, int32_t *chunk_elems, int32_t *block_thread
     if (!p) return fail(CC_ERR_NULL, "cc_plan_layout: plan is NULL");
     if (chunk_elems) *chunk_elems = p->lay().chunk_elems;
     if (block_threads) *block_threads = p->lay().block;
-    if (cache_policy) *cache_policy = p->resident ? CC_CACHE_RESIDENT : CC_CACHE_STREAMING;
+    if (cache_policy) *cache_policy = p->mem;
     return CC_OK;
 }
 
 int cc_plan_set_cache_policy(cc_plan *p, int32_t policy)
 {
     if (!p) return fail(CC_ERR_NULL, "cc_plan_set_cache_policy: plan is NULL");
-    if (policy != CC_CACHE_AUTO && policy != CC_CACHE_STREAMING && policy != CC_CACHE_RESIDENT)
+    if (policy != CC_CACHE_AUTO && policy != CC_CACHE_STREAMING && policy != CC_CACHE_RESIDENT && policy != CC_CACHE_WRITE_THROUGH)
         return fail(CC_ERR_ARG, "cc_plan_set_cache_policy: policy = %d", policy);
     p->cache_policy = policy;
     resolve_schedule(p);
@@ -645,7 +641,8 @@ int cc_fused_adam_step_static(const cc_tensor *t, int32_t R, const cc_hparams *h
     d.wd = t->weight_decay;
     const unsigned grid = (unsigned)((t->numel + (uint64_t)kSmallChunkElems - 1) / (uint64_t)kSmallChunkElems);
     const int mode = (hp->skip_mode == 1 ? kModeGuard : 0) | (hp->adam_mode == 0 ? kModeL2 : 0);
-    launch_fused_adam_flat_f16(d, R, grid, false, s, fs, flag, st, mode);
+    const int32_t mem = auto_cache_policy(t->numel * (2u * (uint64_t)R + 26u));          // the plans' AUTO rule
+    launch_fused_adam_flat_f16(d, R, grid, mem, s, fs, flag, st, mode);
     return launched("fused_adam_flat_kernel");
 }
 
@@ -826,12 +823,14 @@ int cc_plan_autotune(cc_plan *p, const cc_hparams *hp, int32_t optimizer, int32_
     try {
         const int32_t current = p->lay().chunk_elems;
         cand.push_back(Candidate{current, CC_SCHEDULE_PER_CHUNK, 0u, CC_CACHE_STREAMING});
-        if (p->lay().block == kSmallBlock) cand.push_back(Candidate{current, CC_SCHEDULE_PER_CHUNK, 0u, CC_CACHE_RESIDENT});
+        if (p->lay().block == kSmallBlock)
+            for (int32_t c : {CC_CACHE_RESIDENT, CC_CACHE_WRITE_THROUGH}) cand.push_back(Candidate{current, CC_SCHEDULE_PER_CHUNK, 0u, c});
         for (const Layout &L : p->layouts) {
             if (L.chunks == 0) continue;
             if (L.chunk_elems != current) {
                 cand.push_back(Candidate{L.chunk_elems, CC_SCHEDULE_PER_CHUNK, 0u, CC_CACHE_STREAMING});
-                if (L.block == kSmallBlock) cand.push_back(Candidate{L.chunk_elems, CC_SCHEDULE_PER_CHUNK, 0u, CC_CACHE_RESIDENT});
+                if (L.block == kSmallBlock)
+                    for (int32_t c : {CC_CACHE_RESIDENT, CC_CACHE_WRITE_THROUGH}) cand.push_back(Candidate{L.chunk_elems, CC_SCHEDULE_PER_CHUNK, 0u, c});
             }
             if (L.chunk_elems == kDefaultChunkElems) {
                 const unsigned cus = (unsigned)p->cus;
@@ -897,7 +896,8 @@ int cc_pattern_probe(const cc_tensor *t, int32_t R, int32_t what, int32_t cache_
     if (!t || !d_sink) return fail(CC_ERR_NULL, "cc_pattern_probe: NULL argument");
     if (R != 4 && R != 8) return fail(CC_ERR_ARG, "cc_pattern_probe: R = %d (4 or 8)", R);
     if (what < 0 || what > 3) return fail(CC_ERR_ARG, "cc_pattern_probe: what = %d outside 0..3", what);
-    if (cache_policy != CC_CACHE_STREAMING && cache_policy != CC_CACHE_RESIDENT) return fail(CC_ERR_ARG, "cc_pattern_probe: cache_policy = %d", cache_policy);
+    if (cache_policy != CC_CACHE_STREAMING && cache_policy != CC_CACHE_RESIDENT && cache_policy != CC_CACHE_WRITE_THROUGH)
+        return fail(CC_ERR_ARG, "cc_pattern_probe: cache_policy = %d", cache_policy);
     if (t->numel == 0 || t->numel % kSmallChunkElems != 0 || t->numel / kSmallChunkElems > 0x7fffffffull)
         return fail(CC_ERR_ARG, "cc_pattern_probe: numel = %llu must be a positive multiple of %d", (unsigned long long)t->numel, kSmallChunkElems);
     const void *ptrs[7] = {t->w_in, t->m_in, t->v_in, t->w_out, t->m_out, t->v_out, t->w16_out};
@@ -920,6 +920,7 @@ int cc_pattern_probe(const cc_tensor *t, int32_t R, int32_t what, int32_t cache_
 #define PROBE(r, w, M) hipLaunchKernelGGL((pattern_probe_kernel<r, w, kSmallBlock, M>), grid, block, 0, st, d, s, d_sink)
 #define PROBE_W(r, M) switch (what) { case 0: PROBE(r, 0, M); break; case 1: PROBE(r, 1, M); break; case 2: PROBE(r, 2, M); break; default: PROBE(r, 3, M); break; }
     if (cache_policy == CC_CACHE_RESIDENT) { if (R == 4) { PROBE_W(4, Resident) } else { PROBE_W(8, Resident) } }
+    else if (cache_policy == CC_CACHE_WRITE_THROUGH) { if (R == 4) { PROBE_W(4, WriteThrough) } else { PROBE_W(8, WriteThrough) } }
     else { if (R == 4) { PROBE_W(4, Streaming) } else { PROBE_W(8, Streaming) } }
 #undef PROBE_W
 #undef PROBE

@@ -107,35 +107,45 @@ __device__ __forceinline__ gcbytes chunk_base(const void *p, uint64_t byte_off) 
 __device__ __forceinline__ gbytes chunk_base(void *p, uint64_t byte_off) { return (gbytes)p + byte_off; }
 
 // Cache policy of a kernel's vector accesses.
-//   Streaming: non-temporal hints on every access.  Right for shards that do not fit on chip: the data is not touched
-//              again before it has left every cache (+3 % with one workgroup per chunk, +7 % on the stores under the
-//              ordered schedule).
-//   Resident:  plain accesses, for shards whose whole step (inputs and outputs of two consecutive steps, which
-//              ping-pong between two copies) fits the 256 MB Infinity Cache.  On the memory pattern of a 2^20-element
-//              step they were 0.3-0.8 us faster than non-temporal ones on some machines and 0.3-0.6 us slower on
-//              others, so plans use them only on request (or when the tuner measures them faster).
-struct Streaming { static constexpr bool kNonTemporal = true; };
-struct Resident { static constexpr bool kNonTemporal = false; };
+//   Streaming:    non-temporal hints on every access.  Right for shards far beyond what the chip holds: the data is
+//                 not touched again before it has left every cache (+3 % with one workgroup per chunk, +7 % on the
+//                 stores under the ordered schedule).
+//   Resident:     plain loads, and stores that are written through to the device's coherence point (the sc1 bit), for
+//                 shards whose whole step (inputs and outputs of two consecutive steps, which ping-pong between two
+//                 copies) fits the 256 MB Infinity Cache.  The next step then finds what this one wrote on chip, and
+//                 no dirty lines are left in the L2s for the end of the kernel to write back.  On the memory pattern
+//                 of a 2^20-element step: 5.2 us, against 6.6-6.8 us for every combination of plain or non-temporal
+//                 loads with plain or non-temporal stores on the same machine.
+//   WriteThrough: non-temporal loads with the written-through stores, for shards of a few times the Infinity Cache.
+//                 Memory pattern of a 2^24-element step with four slices (570 MB): 72 us, against 93 us for Streaming
+//                 and 102 us for Resident; at 2^20 elements it is the slowest of the three (7.1 us), at 2^26 it is 2 %
+//                 behind Streaming.
+// The compiler has no spelling for a vector store with the sc1 bit, hence the asm; the s_nop behind each store is the
+// wait the hardware asks for between a store of more than 64 bits and a vector instruction that overwrites the
+// registers holding its data, which the compiler inserts for its own stores but cannot for one it does not see.
+struct Streaming { static constexpr bool kLoadNonTemporal = true, kStoreThrough = false; };
+struct Resident { static constexpr bool kLoadNonTemporal = false, kStoreThrough = true; };
+struct WriteThrough { static constexpr bool kLoadNonTemporal = true, kStoreThrough = true; };
 
 template <class Mem> __device__ __forceinline__ f32x4 ld_f32x4(gcbytes b, uint32_t off)
 {
-    if (Mem::kNonTemporal) return __builtin_nontemporal_load((const CCF_GLOBAL f32x4 *)(b + off));
+    if (Mem::kLoadNonTemporal) return __builtin_nontemporal_load((const CCF_GLOBAL f32x4 *)(b + off));
     return *(const CCF_GLOBAL f32x4 *)(b + off);
 }
 template <class Mem> __device__ __forceinline__ f16x4 ld_f16x4(gcbytes b, uint32_t off)
 {
-    if (Mem::kNonTemporal) return __builtin_nontemporal_load((const CCF_GLOBAL f16x4 *)(b + off));
+    if (Mem::kLoadNonTemporal) return __builtin_nontemporal_load((const CCF_GLOBAL f16x4 *)(b + off));
     return *(const CCF_GLOBAL f16x4 *)(b + off);
 }
 template <class Mem> __device__ __forceinline__ void st_f32x4(gbytes b, uint32_t off, f32x4 x)
 {
-    if (Mem::kNonTemporal) __builtin_nontemporal_store(x, (CCF_GLOBAL f32x4 *)(b + off));
-    else *(CCF_GLOBAL f32x4 *)(b + off) = x;
+    if (!Mem::kStoreThrough) __builtin_nontemporal_store(x, (CCF_GLOBAL f32x4 *)(b + off));
+    else asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" : : "v"(b + off), "v"(x) : "memory");
 }
 template <class Mem> __device__ __forceinline__ void st_f16x4(gbytes b, uint32_t off, f16x4 x)
 {
-    if (Mem::kNonTemporal) __builtin_nontemporal_store(x, (CCF_GLOBAL f16x4 *)(b + off));
-    else *(CCF_GLOBAL f16x4 *)(b + off) = x;
+    if (!Mem::kStoreThrough) __builtin_nontemporal_store(x, (CCF_GLOBAL f16x4 *)(b + off));
+    else asm volatile("global_store_dwordx2 %0, %1, off sc1\n\ts_nop 1" : : "v"(b + off), "v"(x) : "memory");
 }
 __device__ __forceinline__ float ld_f32(gcbytes b, uint32_t off) { return *(const CCF_GLOBAL float *)(b + off); }
 __device__ __forceinline__ float ld_f16(gcbytes b, uint32_t off) { return (float)*(const CCF_GLOBAL _Float16 *)(b + off); }

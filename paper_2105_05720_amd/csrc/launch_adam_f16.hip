@@ -33,10 +33,11 @@ void launch_flat_mode(const DevTensor &t, int R, unsigned grid, const StepScalar
 
 }  // namespace
 
-void launch_fused_adam_flat_f16(const DevTensor &t, int R, unsigned grid, bool resident, const StepScalars &s, FlagScratch *fs,
+void launch_fused_adam_flat_f16(const DevTensor &t, int R, unsigned grid, int32_t mem, const StepScalars &s, FlagScratch *fs,
                                 int32_t *flag, hipStream_t st, int mode)
 {
-    if (resident) launch_flat_mode<Resident>(t, R, grid, s, fs, flag, st, mode);
+    if (mem == CC_CACHE_RESIDENT) launch_flat_mode<Resident>(t, R, grid, s, fs, flag, st, mode);
+    else if (mem == CC_CACHE_WRITE_THROUGH) launch_flat_mode<WriteThrough>(t, R, grid, s, fs, flag, st, mode);
     else launch_flat_mode<Streaming>(t, R, grid, s, fs, flag, st, mode);
 }
 

@@ -21,11 +21,17 @@ constexpr int32_t kMaxChunkElems = 1 << 24;      // lane offsets inside a chunk 
 constexpr int kBigBlock = 512, kSmallBlock = 128;
 constexpr int kOrderedMaxF32Slices = 8;           // fp32 slices: the ordered schedule wins up to 8 (config-2 list: 3.18 against 3.41 ms), at 16 two chunks spill
 constexpr int64_t kOrderedMinChunksPerCu = 8;    // below this many chunks per compute unit a plan keeps one workgroup per chunk
-// AUTO cache policy: plain instead of non-temporal accesses when the step's buffers (R gradient slices, both copies of
-// w, m, v and of the fp16 weights) total between these bounds, i.e. no longer fit the L2s but fit the 256 MB Infinity
-// Cache.  Size sweep at R = 8: 14.6 against 16.1 us at 2^21 elements (88 MB), 27.7 against 29.4 us at 2^22 (176 MB),
-// but 66.9 against 59.5 us at 2^23 (352 MB); below 64 MB the two differ by less than their spread from machine to machine.
-constexpr uint64_t kResidentMinBytes = 64ull << 20, kResidentMaxBytes = 200ull << 20;
+// AUTO cache policy: plain loads and write-through stores instead of non-temporal accesses while the step's buffers (R
+// gradient slices, both copies of w, m, v and of the fp16 weights) total less than this, i.e. fit the 256 MB Infinity
+// Cache.  Size sweep at R = 8, us per step: 6.2 against 7.9 at 2^20 elements (44 MB), 14.9 against 15.8 at 2^21 (88 MB),
+// 27.6 against 29.6 at 2^22 (176 MB), but 68.1 against 60.2 at 2^23 (352 MB); below 2^18 the two are within 0.2 us.
+constexpr uint64_t kResidentMaxBytes = 200ull << 20;
+// ... and non-temporal loads with write-through stores from there up to this total (see WriteThrough).
+constexpr uint64_t kWriteThroughMaxBytes = 900ull << 20;
+inline int32_t auto_cache_policy(uint64_t footprint)
+{
+    return footprint < kResidentMaxBytes ? CC_CACHE_RESIDENT : footprint < kWriteThroughMaxBytes ? CC_CACHE_WRITE_THROUGH : CC_CACHE_STREAMING;
+}
 
 
 // Records the message for cc_last_error() on this thread and returns the code.
@@ -62,7 +68,7 @@ struct cc_plan {
     bool ordered = false;                   // large shards: persistent workgroups take chunks in table order
     int32_t schedule = CC_SCHEDULE_AUTO;    // what the caller asked for
     unsigned ordered_grid = 0;              // workgroups of the ordered schedule (one per compute unit unless set)
-    bool resident = false;                  // plain instead of non-temporal accesses (small-chunk layout only)
+    int32_t mem = CC_CACHE_STREAMING;       // the policy in use (other than STREAMING: small-chunk layouts only)
     int32_t cache_policy = CC_CACHE_AUTO;   // what the caller asked for
     int32_t cus = 0;                        // compute units of the device the plan was created on
     int32_t single = -1;                    // index of the only tensor with elements, or -1 if there are several (or none)
@@ -95,11 +101,12 @@ inline unsigned ordered_grid(const cc_plan *p)
 #define FOR_EACH_R(X) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13) X(14) X(15) X(16)
 
 // Every per-chunk streaming kernel exists for two workgroup sizes, and the small one for both cache policies; the
-// plan's layout and residency pick one.  CALL sees BLK (int) and MEM (Streaming or Resident).
+// plan's layout and policy pick one.  CALL sees BLK (int) and MEM (Streaming, Resident or WriteThrough).
 #define BY_BLOCK(p, CALL)                                                                   \
     do {                                                                                    \
         if ((p)->lay().block == kBigBlock) { constexpr int BLK = kBigBlock; typedef Streaming MEM; CALL; }        \
-        else if ((p)->resident) { constexpr int BLK = kSmallBlock; typedef Resident MEM; CALL; }                   \
+        else if ((p)->mem == CC_CACHE_RESIDENT) { constexpr int BLK = kSmallBlock; typedef Resident MEM; CALL; }  \
+        else if ((p)->mem == CC_CACHE_WRITE_THROUGH) { constexpr int BLK = kSmallBlock; typedef WriteThrough MEM; CALL; } \
         else { constexpr int BLK = kSmallBlock; typedef Streaming MEM; CALL; }                                    \
     } while (0)
 
@@ -129,7 +136,7 @@ void launch_adam_from_sum(const cc_plan *p, const StepScalars &s, const int32_t 
 int cast_launch(cc_plan *p, const StepScalars &s, const int32_t *flag, hipStream_t st, int guarded);
 int clear_flag(int32_t *flag, hipStream_t st);
 // One fp16-slice tensor, no plan: one workgroup of kSmallBlock per kSmallChunkElems elements, counted on `fs`.
-void launch_fused_adam_flat_f16(const DevTensor &t, int R, unsigned grid, bool resident, const StepScalars &s, FlagScratch *fs,
+void launch_fused_adam_flat_f16(const DevTensor &t, int R, unsigned grid, int32_t mem, const StepScalars &s, FlagScratch *fs,
                                 int32_t *flag, hipStream_t st, int mode);
 
 }  // namespace ccf

@@ -51,7 +51,7 @@ def replay_unfused_and_compare(shard, unfused_fn, ghp, label):
 def test_config1_adam_flat_1m_three_steps_whole():
     cfg = W.config(1)
     shard = shard_for(cfg)
-    assert cc.cc_plan_layout(shard.plans[0]) == (1024, 128, cc.CC_CACHE_STREAMING)       # what bench.py times
+    assert cc.cc_plan_layout(shard.plans[0]) == (1024, 128, cc.CC_CACHE_RESIDENT)        # what bench.py times
     ost = OracleState(shard, [0])
     hps = [hp_of(cfg, t) for t in (1, 2, 3)]
     rep = run_steps(shard, ost, cc.cc_fused_adam_step, oracle.adam_step, hps, "config 1",

@@ -33,7 +33,7 @@ def run_shape(fn, ofn, chunk, policy, R=4, grad_dtype=torch.float16, steps=2, nu
         cc.cc_plan_set_chunk_elems(p, chunk)
         cc.cc_plan_set_cache_policy(p, policy)
         assert cc.cc_plan_layout(p)[0] == chunk
-        want = cc.CC_CACHE_RESIDENT if (policy == cc.CC_CACHE_RESIDENT and chunk < 4096) else cc.CC_CACHE_STREAMING
+        want = policy if chunk < 4096 else cc.CC_CACHE_STREAMING
         assert cc.cc_plan_layout(p)[2] == want
     seeded_state(sh, 5)
     ost = OracleState(sh, range(len(numels)))
@@ -47,8 +47,8 @@ def run_shape(fn, ofn, chunk, policy, R=4, grad_dtype=torch.float16, steps=2, nu
 @pytest.mark.parametrize("fn,ofn", [(cc.cc_fused_adam_step, oracle.adam_step), (cc.cc_unfused_adam_step, oracle.adam_step)])
 def test_adam_bits_do_not_depend_on_chunk_size_or_cache_policy(fn, ofn):
     ref = run_shape(fn, ofn, 1024, cc.CC_CACHE_STREAMING)
-    for chunk, policy in ((1024, cc.CC_CACHE_RESIDENT), (4096, cc.CC_CACHE_STREAMING), (16384, cc.CC_CACHE_STREAMING),
-                          (4096, cc.CC_CACHE_RESIDENT)):
+    for chunk, policy in ((1024, cc.CC_CACHE_RESIDENT), (1024, cc.CC_CACHE_WRITE_THROUGH), (4096, cc.CC_CACHE_STREAMING),
+                          (16384, cc.CC_CACHE_STREAMING), (4096, cc.CC_CACHE_RESIDENT)):
         got = run_shape(fn, ofn, chunk, policy)
         assert all(torch.equal(a, b) for a, b in zip(ref, got)), "chunk %d policy %d changes Adam's bits" % (chunk, policy)
 
@@ -56,8 +56,8 @@ def test_adam_bits_do_not_depend_on_chunk_size_or_cache_policy(fn, ofn):
 @pytest.mark.parametrize("fn", [cc.cc_fused_lamb_step, cc.cc_unfused_lamb_step])
 def test_lamb_every_chunk_size_and_policy_against_oracle(fn):
     per_chunk = {}
-    for chunk, policy in ((1024, cc.CC_CACHE_STREAMING), (1024, cc.CC_CACHE_RESIDENT), (4096, cc.CC_CACHE_STREAMING),
-                          (16384, cc.CC_CACHE_STREAMING)):
+    for chunk, policy in ((1024, cc.CC_CACHE_STREAMING), (1024, cc.CC_CACHE_RESIDENT), (1024, cc.CC_CACHE_WRITE_THROUGH),
+                          (4096, cc.CC_CACHE_STREAMING), (16384, cc.CC_CACHE_STREAMING)):
         got = run_shape(fn, oracle.lamb_step, chunk, policy)
         if chunk in per_chunk:          # same chunk size, other cache policy: the same bits
             assert all(torch.equal(a, b) for a, b in zip(per_chunk[chunk], got))
@@ -69,20 +69,22 @@ def test_resident_policy_every_kind_of_R_and_fp32_slices(R):
     for gd in (torch.float16, torch.float32):
         a = run_shape(cc.cc_fused_adam_step, oracle.adam_step, 1024, cc.CC_CACHE_RESIDENT, R=R, grad_dtype=gd, steps=1)
         b = run_shape(cc.cc_fused_adam_step, oracle.adam_step, 1024, cc.CC_CACHE_STREAMING, R=R, grad_dtype=gd, steps=1)
-        assert all(torch.equal(x, y) for x, y in zip(a, b))
+        c = run_shape(cc.cc_fused_adam_step, oracle.adam_step, 1024, cc.CC_CACHE_WRITE_THROUGH, R=R, grad_dtype=gd, steps=1)
+        assert all(torch.equal(x, y) and torch.equal(x, z) for x, y, z in zip(a, b, c))
 
 
 def test_single_tensor_plan_resident_and_streaming():
     """One tensor: the table-free kernel, both policies, against the oracle (2^17 + a ragged end)."""
-    for policy in (cc.CC_CACHE_RESIDENT, cc.CC_CACHE_STREAMING):
+    for policy in (cc.CC_CACHE_RESIDENT, cc.CC_CACHE_STREAMING, cc.CC_CACHE_WRITE_THROUGH):
         run_shape(cc.cc_fused_adam_step, oracle.adam_step, 1024, policy, numels=[(1 << 17) + 5], steps=2)
 
 
 def test_auto_policy_and_layout_rules():
-    small = Shard([1 << 20], [0.0], 4, align_elems=8)
-    assert cc.cc_plan_layout(small.plans[0]) == (1024, 128, cc.CC_CACHE_STREAMING)
+    small = Shard([1 << 20], [0.0], 4, align_elems=8)                                  # 36 MB of buffers
+    assert cc.cc_plan_layout(small.plans[0]) == (1024, 128, cc.CC_CACHE_RESIDENT)
+    cc.cc_plan_set_cache_policy(small.plans[0], cc.CC_CACHE_STREAMING)
+    assert cc.cc_plan_layout(small.plans[0])[2] == cc.CC_CACHE_STREAMING
     cc.cc_plan_set_cache_policy(small.plans[0], cc.CC_CACHE_RESIDENT)
-    assert cc.cc_plan_layout(small.plans[0])[2] == cc.CC_CACHE_RESIDENT
     cc.cc_plan_set_chunk_elems(small.plans[0], 4096)
     assert cc.cc_plan_layout(small.plans[0]) == (4096, 512, cc.CC_CACHE_STREAMING)     # resident exists for 128-thread workgroups only
     with pytest.raises(cc.CcError) as e:
@@ -92,12 +94,16 @@ def test_auto_policy_and_layout_rules():
         cc.cc_plan_set_cache_policy(small.plans[0], 9)
     cc.cc_plan_set_chunk_elems(small.plans[0], 0)
     assert cc.cc_plan_layout(small.plans[0]) == (1024, 128, cc.CC_CACHE_RESIDENT)
+    cc.cc_plan_set_cache_policy(small.plans[0], cc.CC_CACHE_STREAMING)
     cc.cc_plan_set_cache_policy(small.plans[0], cc.CC_CACHE_AUTO)
-    assert cc.cc_plan_layout(small.plans[0])[2] == cc.CC_CACHE_STREAMING
+    assert cc.cc_plan_layout(small.plans[0])[2] == cc.CC_CACHE_RESIDENT
     small.destroy()
-    mid = Shard([1 << 21], [0.0], 8, align_elems=8, unfused=False)                      # 88 MB of buffers: Infinity Cache, not L2
+    mid = Shard([1 << 22], [0.0], 8, align_elems=8, unfused=False)                      # 176 MB of buffers: still inside the Infinity Cache
     assert cc.cc_plan_layout(mid.plans[0]) == (1024, 128, cc.CC_CACHE_RESIDENT)
     mid.destroy()
+    big = Shard([1 << 23], [0.0], 8, align_elems=8, unfused=False)                      # 352 MB: streams in, writes through
+    assert cc.cc_plan_layout(big.plans[0]) == (1024, 128, cc.CC_CACHE_WRITE_THROUGH)
+    big.destroy()
     fixed = Shard([1 << 16], [0.0], 2, chunk_elems=2048, align_elems=8)                 # a caller's own chunk size: that one only
     assert cc.cc_plan_layout(fixed.plans[0])[:2] == (2048, 128)
     with pytest.raises(cc.CcError):
