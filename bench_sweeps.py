@@ -105,7 +105,9 @@ def best_shapes(shard: Shard, R: int, gb: int, n: int, steps: int, which=None):
                 continue
             times[label] = round(time_step(shard, fn, steps), 3)
         label = min(times, key=times.get)
-        row[name] = {"us": times[label], "shape": label, "GB/s": round(bpp * n / times[label] / 1e3, 1), "all": times}
+        set_shape(shard, 0, cc.CC_SCHEDULE_AUTO, cc.CC_CACHE_AUTO)       # what a caller gets without choosing anything
+        auto = round(time_step(shard, fn, steps), 3)
+        row[name] = {"us": times[label], "shape": label, "GB/s": round(bpp * n / times[label] / 1e3, 1), "all": times, "auto_us": auto}
     return row
 
 
@@ -131,18 +133,21 @@ def mode_sweep(argv) -> int:
         print(json.dumps(row), flush=True)
     if args.markdown:
         with open(args.markdown, "w") as f:
-            f.write("| log2 N | fused Adam us (shape) | GB/s | % of 8 TB/s | unfused Adam us | fused speed-up | fused LAMB us (shape) | GB/s | unfused LAMB us | speed-up |\n")
-            f.write("|---|---|---|---|---|---|---|---|---|---|\n")
+            f.write("| log2 N | fused Adam us (shape) | GB/s | % of 8 TB/s | unfused Adam us | fused speed-up | fused LAMB us (shape) | GB/s | % of 8 TB/s | unfused LAMB us | speed-up |\n")
+            f.write("|---|---|---|---|---|---|---|---|---|---|---|\n")
             for r in rows:
-                f.write("| %d | %.2f (%s) | %.0f | %.1f | %.2f | %.2fx | %.2f (%s) | %.0f | %.2f | %.2fx |\n" % (
+                f.write("| %d | %.2f (%s) | %.0f | %.1f | %.2f | %.2fx | %.2f (%s) | %.0f | %.1f | %.2f | %.2fx |\n" % (
                     r["log2"], r["fused_adam"]["us"], r["fused_adam"]["shape"], r["fused_adam"]["GB/s"], r["fused_adam"]["GB/s"] / 80.0,
                     r["unfused_adam"]["us"], r["adam_fused_over_unfused"], r["fused_lamb"]["us"], r["fused_lamb"]["shape"],
-                    r["fused_lamb"]["GB/s"], r["unfused_lamb"]["us"], r["lamb_fused_over_unfused"]))
-            f.write("\nFused Adam, microseconds per step under every launch shape (chunk elements, schedule, cache policy):\n\n")
+                    r["fused_lamb"]["GB/s"], r["fused_lamb"]["GB/s"] / 80.0, r["unfused_lamb"]["us"], r["lamb_fused_over_unfused"]))
             labels = [s[3] for s in SHAPES]
-            f.write("| log2 N | " + " | ".join(labels) + " |\n|---|" + "---|" * len(labels) + "\n")
-            for r in rows:
-                f.write("| %d | " % r["log2"] + " | ".join("%.2f" % r["fused_adam"]["all"][l] if l in r["fused_adam"]["all"] else "-" for l in labels) + " |\n")
+            for path, title in (("fused_adam", "Fused Adam"), ("fused_lamb", "Fused LAMB")):
+                f.write("\n%s, microseconds per step under every launch shape (chunk elements, schedule, cache policy) and under the "
+                        "library's own choice (no cc_plan_set_* call):\n\n" % title)
+                f.write("| log2 N | " + " | ".join(labels) + " | automatic | automatic / best |\n|---|" + "---|" * (len(labels) + 2) + "\n")
+                for r in rows:
+                    f.write("| %d | " % r["log2"] + " | ".join("%.2f" % r[path]["all"][l] if l in r[path]["all"] else "-" for l in labels)
+                            + " | %.2f | %.3f |\n" % (r[path]["auto_us"], r[path]["auto_us"] / r[path]["us"]))
     return 0
 
 

@@ -166,10 +166,13 @@ int cc_plan_layout(const cc_plan *plan, int32_t *chunk_elems, int32_t *block_thr
  * Cache policy of the streaming kernels' accesses.  STREAMING marks every access non-temporal (right for shards far
  * beyond what the chip holds).  RESIDENT uses plain loads and write-through stores, so that a shard whose whole step
  * fits the 256 MB Infinity Cache finds its inputs on chip in the next step.  WRITE_THROUGH keeps the non-temporal loads
- * and writes the stores through, for shards of a few times that cache.  The last two exist for 128-thread workgroups
- * (chunks below 4096 elements) and are ignored otherwise.  Results do not depend on the policy.  AUTO (default) goes by
- * the bytes of the step's buffers: RESIDENT below 200 MiB (4-20 % faster than STREAMING between 2^18 and 2^22 elements
- * in the size sweep, equal below), WRITE_THROUGH from there to 900 MiB (8-11 % faster at 2^23 and 2^24 elements), STREAMING beyond.  cc_plan_autotune tries all.
+ * and writes the stores through, for shards of which one launch's output still about fits that cache.  The last two
+ * exist for 128-thread workgroups (chunks below 4096 elements) and are ignored otherwise.  Results do not depend on
+ * the policy.  AUTO (default): RESIDENT while the step's buffers total less than 200 MiB (4-20 % faster than STREAMING
+ * between 2^18 and 2^22 elements in the size sweep, equal below); else WRITE_THROUGH while a launch stores less than
+ * 288 MiB (the Adam step stores 14 bytes per element: up to 20.5 Mi elements, 8-12 % faster at 2^23 and 2^24; LAMB's
+ * sweeps store 8 and 6: up to 36 Mi elements, and cc_plan_layout reports the Adam step's policy); else STREAMING.
+ * cc_plan_autotune tries all three.
  */
 typedef enum cc_cache_policy { CC_CACHE_AUTO = 0, CC_CACHE_STREAMING = 1, CC_CACHE_RESIDENT = 2, CC_CACHE_WRITE_THROUGH = 3 } cc_cache_policy;
 int cc_plan_set_cache_policy(cc_plan *plan, int32_t policy);

@@ -124,9 +124,13 @@ void resolve_schedule(cc_plan *p)
     else if (p->schedule == CC_SCHEDULE_PER_CHUNK) p->ordered = false;
     else p->ordered = L.chunks >= kOrderedMinChunksPerCu * (int64_t)p->cus && !(p->grad_f32 && p->R > kOrderedMaxF32Slices);
     if (L.chunk_elems != kDefaultChunkElems || L.chunks == 0) p->ordered = false;
-    if (p->cache_policy != CC_CACHE_AUTO) p->mem = p->cache_policy;
-    else p->mem = auto_cache_policy(p->numel * ((p->grad_f32 ? 4u : 2u) * (uint64_t)p->R + 12u + 14u));
-    if (L.block != kSmallBlock || p->ordered) p->mem = CC_CACHE_STREAMING;
+    if (p->cache_policy != CC_CACHE_AUTO) p->mem = p->mem_lamb = p->cache_policy;
+    else {
+        const uint64_t footprint = p->numel * ((p->grad_f32 ? 4u : 2u) * (uint64_t)p->R + 12u + 14u);
+        p->mem = auto_cache_policy(footprint, p->numel * kAdamStoreBytes);
+        p->mem_lamb = auto_cache_policy(footprint, p->numel * kLambStoreBytes);
+    }
+    if (L.block != kSmallBlock || p->ordered) p->mem = p->mem_lamb = CC_CACHE_STREAMING;
 }
 
 void free_layout(Layout &L)
@@ -641,7 +645,7 @@ int cc_fused_adam_step_static(const cc_tensor *t, int32_t R, const cc_hparams *h
     d.wd = t->weight_decay;
     const unsigned grid = (unsigned)((t->numel + (uint64_t)kSmallChunkElems - 1) / (uint64_t)kSmallChunkElems);
     const int mode = (hp->skip_mode == 1 ? kModeGuard : 0) | (hp->adam_mode == 0 ? kModeL2 : 0);
-    const int32_t mem = auto_cache_policy(t->numel * (2u * (uint64_t)R + 26u));          // the plans' AUTO rule
+    const int32_t mem = auto_cache_policy(t->numel * (2u * (uint64_t)R + 26u), t->numel * kAdamStoreBytes);   // the plans' AUTO rule
     launch_fused_adam_flat_f16(d, R, grid, mem, s, fs, flag, st, mode);
     return launched("fused_adam_flat_kernel");
 }

@@ -26,11 +26,15 @@ constexpr int64_t kOrderedMinChunksPerCu = 8;    // below this many chunks per c
 // Cache.  Size sweep at R = 8, us per step: 6.2 against 7.9 at 2^20 elements (44 MB), 14.9 against 15.8 at 2^21 (88 MB),
 // 27.6 against 29.6 at 2^22 (176 MB), but 68.1 against 60.2 at 2^23 (352 MB); below 2^18 the two are within 0.2 us.
 constexpr uint64_t kResidentMaxBytes = 200ull << 20;
-// ... and non-temporal loads with write-through stores from there up to this total (see WriteThrough).
-constexpr uint64_t kWriteThroughMaxBytes = 900ull << 20;
-inline int32_t auto_cache_policy(uint64_t footprint)
+// ... and from there on non-temporal loads with write-through stores while one kernel stores less than this (see
+// WriteThrough): what a launch writes then about fits the Infinity Cache.  Fused Adam (14 B stored per element) at
+// R = 8: 141 against 147 us at 20 Mi elements, 160 against 157 us at 22 Mi; fused LAMB (8 B in its first sweep, 6 B in
+// its second): 318 against 338 us at 36 Mi elements, 373 against 368 us at 40 Mi.
+constexpr uint64_t kWriteThroughMaxStoreBytes = 288ull << 20;
+constexpr uint32_t kAdamStoreBytes = 14, kLambStoreBytes = 8;      // per element: w', m', v', w16 / m', v'
+inline int32_t auto_cache_policy(uint64_t footprint, uint64_t stored)
 {
-    return footprint < kResidentMaxBytes ? CC_CACHE_RESIDENT : footprint < kWriteThroughMaxBytes ? CC_CACHE_WRITE_THROUGH : CC_CACHE_STREAMING;
+    return footprint < kResidentMaxBytes ? CC_CACHE_RESIDENT : stored < kWriteThroughMaxStoreBytes ? CC_CACHE_WRITE_THROUGH : CC_CACHE_STREAMING;
 }
 
 
@@ -69,6 +73,7 @@ struct cc_plan {
     int32_t schedule = CC_SCHEDULE_AUTO;    // what the caller asked for
     unsigned ordered_grid = 0;              // workgroups of the ordered schedule (one per compute unit unless set)
     int32_t mem = CC_CACHE_STREAMING;       // the policy in use (other than STREAMING: small-chunk layouts only)
+    int32_t mem_lamb = CC_CACHE_STREAMING;  // ... by LAMB's sweeps, which store fewer bytes per element
     int32_t cache_policy = CC_CACHE_AUTO;   // what the caller asked for
     int32_t cus = 0;                        // compute units of the device the plan was created on
     int32_t single = -1;                    // index of the only tensor with elements, or -1 if there are several (or none)
@@ -100,14 +105,15 @@ inline unsigned ordered_grid(const cc_plan *p)
 
 #define FOR_EACH_R(X) X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13) X(14) X(15) X(16)
 
-// Every per-chunk streaming kernel exists for two workgroup sizes, and the small one for both cache policies; the
-// plan's layout and policy pick one.  CALL sees BLK (int) and MEM (Streaming, Resident or WriteThrough).
-#define BY_BLOCK(p, CALL)                                                                   \
+// Every per-chunk streaming kernel exists for two workgroup sizes, and the small one for every cache policy; the
+// plan's layout and policy pick one.  The statement given sees BLK (int) and MEM (Streaming, Resident or WriteThrough).
+#define BY_BLOCK(p, ...) BY_BLOCK_MEM(p, (p)->mem, __VA_ARGS__)
+#define BY_BLOCK_MEM(p, mem_, ...)                                                          \
     do {                                                                                    \
-        if ((p)->lay().block == kBigBlock) { constexpr int BLK = kBigBlock; typedef Streaming MEM; CALL; }        \
-        else if ((p)->mem == CC_CACHE_RESIDENT) { constexpr int BLK = kSmallBlock; typedef Resident MEM; CALL; }  \
-        else if ((p)->mem == CC_CACHE_WRITE_THROUGH) { constexpr int BLK = kSmallBlock; typedef WriteThrough MEM; CALL; } \
-        else { constexpr int BLK = kSmallBlock; typedef Streaming MEM; CALL; }                                    \
+        if ((p)->lay().block == kBigBlock) { constexpr int BLK = kBigBlock; typedef Streaming MEM; __VA_ARGS__; }        \
+        else if ((mem_) == CC_CACHE_RESIDENT) { constexpr int BLK = kSmallBlock; typedef Resident MEM; __VA_ARGS__; }    \
+        else if ((mem_) == CC_CACHE_WRITE_THROUGH) { constexpr int BLK = kSmallBlock; typedef WriteThrough MEM; __VA_ARGS__; } \
+        else { constexpr int BLK = kSmallBlock; typedef Streaming MEM; __VA_ARGS__; }                                    \
     } while (0)
 
 // Chunks per ticket of the ordered schedule, by how many bytes a kernel moves per element: one counter serves the

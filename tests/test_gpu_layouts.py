@@ -104,6 +104,10 @@ def test_auto_policy_and_layout_rules():
     big = Shard([1 << 23], [0.0], 8, align_elems=8, unfused=False)                      # 352 MB: streams in, writes through
     assert cc.cc_plan_layout(big.plans[0]) == (1024, 128, cc.CC_CACHE_WRITE_THROUGH)
     big.destroy()
+    for mi, want in ((20, cc.CC_CACHE_WRITE_THROUGH), (21, cc.CC_CACHE_STREAMING)):     # 14 B stored per element against 288 MiB
+        edge = Shard([mi << 20], [0.0], 2, align_elems=8, unfused=False)
+        assert cc.cc_plan_layout(edge.plans[0]) == (1024, 128, want)
+        edge.destroy()
     fixed = Shard([1 << 16], [0.0], 2, chunk_elems=2048, align_elems=8)                 # a caller's own chunk size: that one only
     assert cc.cc_plan_layout(fixed.plans[0])[:2] == (2048, 128)
     with pytest.raises(cc.CcError):
@@ -139,14 +143,16 @@ def test_unfused_steps_need_the_reserved_buffer_and_never_allocate():
     sh.destroy(); ref.destroy()
 
 
+@pytest.mark.parametrize("log2n,R,policy", [(21, 8, cc.CC_CACHE_RESIDENT), (23, 2, cc.CC_CACHE_WRITE_THROUGH)])
 @pytest.mark.parametrize("fn,ofn", [(cc.cc_fused_adam_step, oracle.adam_step), (cc.cc_fused_lamb_step, oracle.lamb_step)])
-def test_mid_size_shard_under_the_automatic_cache_policy(fn, ofn):
-    """2^21 elements with R = 8: 88 MB of buffers, where AUTO drops the non-temporal hints; two steps, every element."""
-    n = 1 << 21
-    sh = Shard([n - 4096 * 100 - 3, 4096 * 100 + 3], [0.01, 0.0], 8, unfused=False)
-    assert cc.cc_plan_layout(sh.plans[0]) == (1024, 128, cc.CC_CACHE_RESIDENT)
+def test_mid_size_shard_under_the_automatic_cache_policy(fn, ofn, log2n, R, policy):
+    """2^21 elements with R = 8 (88 MB of buffers: AUTO keeps the shard on chip) and 2^23 elements with R = 2 (252 MB, of
+    which a launch stores 117 MB: AUTO writes through); two steps, every element against the oracle."""
+    n = 1 << log2n
+    sh = Shard([n - 4096 * 100 - 3, 4096 * 100 + 3], [0.01, 0.0], R, unfused=False)
+    assert cc.cc_plan_layout(sh.plans[0]) == (1024, 128, policy)
     seeded_state(sh, 8)
     ost = OracleState(sh, [0, 1])
-    run_steps(sh, ost, fn, ofn, [hyper_pair(step=t) for t in (1, 2)], "2^21 resident", lambda i: seeded_grads(sh, 800 + i, 1e-3),
-              expect_flags=[0, 0])
+    run_steps(sh, ost, fn, ofn, [hyper_pair(step=t) for t in (1, 2)], "2^%d policy %d" % (log2n, policy),
+              lambda i: seeded_grads(sh, 800 + i, 1e-3), expect_flags=[0, 0])
     sh.destroy()
