@@ -756,8 +756,14 @@ int check_epilogue(const cc_epilogue *e, EpilogueArgs *a)
     return CC_OK;
 }
 
-constexpr int kEpilogueBlock = 512;
-constexpr uint32_t kEpilogueChunk = kEpilogueBlock * 8 * 2;
+constexpr int kEpilogueBlock = 512;             // the unfused pipeline's kernels (64, 128 and 256 threads are 2-8 % slower)
+// The fused kernel spends about half as long on the mask generator's integer arithmetic as on its memory traffic, and
+// overlaps the two best as single-wave workgroups that come and go independently: 78.0 us against 86.0 us with 512
+// threads on the [8, 1024, 3072] tensor (256 threads: 78.5 us; 128: 81.8 us).  Two groups of 8 elements per lane where
+// the call is bound by HBM, one where it stays in the Infinity Cache (its 1/8 slices: 10.0 and 20.9 us against 10.4
+// and 22.3 us with two).
+constexpr int kEpilogueFusedBlock = 64;
+constexpr uint64_t kEpilogueCachedBytes = 200ull << 20;
 
 int epilogue_grid(uint64_t numel, uint32_t chunk, unsigned *grid)
 {
@@ -775,11 +781,17 @@ int cc_fused_epilogue(const cc_epilogue *e, void *stream)
     int rc = check_epilogue(e, &a);
     if (rc) return rc;
     if (e->numel == 0) return CC_OK;
+    const int groups = e->numel * (2u * (uint64_t)e->R + 4u) < kEpilogueCachedBytes ? 1 : 2;
     unsigned grid;
-    if ((rc = epilogue_grid(e->numel, kEpilogueChunk, &grid))) return rc;
+    if ((rc = epilogue_grid(e->numel, (uint32_t)(kEpilogueFusedBlock * 8 * groups), &grid))) return rc;
     hipStream_t st = (hipStream_t)stream;
-    switch (e->R) {
-#define CASE(r) case r: hipLaunchKernelGGL((fused_epilogue_kernel<r, kEpilogueBlock>), dim3(grid), dim3(kEpilogueBlock), 0, st, a); break;
+    if (groups == 2) switch (e->R) {
+#define CASE(r) case r: hipLaunchKernelGGL((fused_epilogue_kernel<r, kEpilogueFusedBlock, 2>), dim3(grid), dim3(kEpilogueFusedBlock), 0, st, a); break;
+        FOR_EACH_R(CASE)
+#undef CASE
+    }
+    else switch (e->R) {
+#define CASE(r) case r: hipLaunchKernelGGL((fused_epilogue_kernel<r, kEpilogueFusedBlock, 1>), dim3(grid), dim3(kEpilogueFusedBlock), 0, st, a); break;
         FOR_EACH_R(CASE)
 #undef CASE
     }

@@ -1399,15 +1399,15 @@ struct FusedEpilogueOp {
     }
 };
 
-template <int R, int BLOCK>
+template <int R, int BLOCK, int GROUPS>
 __global__ __launch_bounds__(BLOCK) void fused_epilogue_kernel(EpilogueArgs a)
 {
-    constexpr uint32_t kChunk = BLOCK * 8 * 2;
+    constexpr uint32_t kChunk = BLOCK * 8 * GROUPS;
     const uint64_t base = (uint64_t)blockIdx.x * kChunk;
     const uint64_t rem = a.numel - base;
     FusedEpilogueOp<R> op;
     op.init(a, base);
-    stream_chunk<BLOCK>(op, rem < kChunk ? (uint32_t)rem : kChunk);
+    stream_chunk<BLOCK, FusedEpilogueOp<R>, GROUPS>(op, rem < kChunk ? (uint32_t)rem : kChunk);
 }
 
 // Unfused pipeline: reduce the R partial outputs into an fp32 buffer (a lane owns 4 elements, so that the fp32

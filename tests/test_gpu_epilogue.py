@@ -114,6 +114,26 @@ def test_epilogue_at_the_paper_size_sampled():
     assert torch.equal(piece.view(torch.int16), out[a:b].view(torch.int16))
 
 
+def test_hbm_bound_call_with_a_ragged_end():
+    """16 slices of 6,000,003 elements are 216 MB per call, beyond what the library treats as cache-resident, so the call
+    takes the launch shape of the large tensors (two groups per workgroup); its halves are small enough for the other
+    shape.  Ranges at the start, across the cut and at the ragged end against the oracle; halves against the whole."""
+    n, H, R, p, seed = 6_000_003, 3072, 16, 0.25, 77
+    partials, bias, residual = make(n, R, H, 12, scale=0.2)
+    out = torch.zeros(n, dtype=torch.float16, device="cuda")
+    cc.cc_fused_epilogue(partials, bias, residual, out, 3072 * 5, H, p, seed)
+    torch.cuda.synchronize()
+    bits = to_np_bits(out)
+    cut = 3_000_008
+    for lo, hi in ((0, 20000), (cut - 10000, cut + 10000), (n - 20003, n)):
+        check(bits, partials, bias, residual, 3072 * 5, p, seed, lo, hi)
+    pieces = torch.zeros(n, dtype=torch.float16, device="cuda")
+    for a, b in ((0, cut), (cut, n)):
+        cc.cc_fused_epilogue([x[a:b] for x in partials], bias, residual[a:b], pieces[a:b], 3072 * 5 + a, H, p, seed)
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int16), pieces.view(torch.int16))
+
+
 def test_the_bound_is_tight():
     """The tolerance is neither loose nor replaceable by the simpler 'one fp16 ulp of the result': on 2 M elements some
     kept elements differ from the oracle by exactly one fp16 ulp at max(|out|, |residual|), none by more (check()), and
