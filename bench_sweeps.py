@@ -3,11 +3,12 @@
   sweep     size sweep of the fused and unfused steps on one flat tensor, 2^10 .. 2^30 elements (the axis of the paper's
             standalone experiment, Section 6.1.1 / Fig. 7), with the launch shape tuned per size
   rsweep    the same for R in {1, 2, 4, 8, 16} and fp16 / fp32 gradient slices at 2^20, 2^24 and 2^28 elements
+  cold      single fused steps with the caches evicted before each one, per cache policy (2^18 .. 2^26 elements)
   epilogue  the fused model-parallel epilogue against its unfused pipeline at the sizes of the paper's standalone
             model-parallel experiment (Section 6.2.1)
   small     where the time of a launch-bound 2^20-element step goes: the step's memory pattern with parts taken away
 
-Steps are replayed from a HIP graph so that small sizes measure the GPU, not the Python caller.  Every mode prints one
+Except in `cold`, steps are replayed from a HIP graph so that small sizes measure the GPU, not the Python caller.  Every mode prints one
 JSON object per row and can write a markdown table (--markdown FILE).
 """
 from __future__ import annotations
@@ -185,6 +186,59 @@ def mode_rsweep(argv) -> int:
     return 0
 
 
+def mode_cold(argv) -> int:
+    """One step at a time with the caches evicted first (a 2 GiB copy), as a training loop sees the optimizer step after a
+    backward pass: median of `reps` event pairs that bracket the step alone, per cache policy and for the automatic choice."""
+    ap = argparse.ArgumentParser(prog="bench.py --mode cold")
+    ap.add_argument("--min-log2", type=int, default=18)
+    ap.add_argument("--max-log2", type=int, default=26)
+    ap.add_argument("--R", type=int, default=8)
+    ap.add_argument("--reps", type=int, default=15)
+    ap.add_argument("--markdown", type=str, default="")
+    args = ap.parse_args(argv)
+    nbytes = 2 << 30
+    src = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+
+    def cold(shard, fn):
+        times = []
+        for i in range(args.reps):
+            cc.cc_copy_probe(dst, src, nbytes)
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            shard.run(fn, cc.Hyper(step=1 + i))
+            b.record()
+            shard.commit()
+            torch.cuda.synchronize()
+            times.append(a.elapsed_time(b) * 1e3)
+        times.sort()
+        return round(times[len(times) // 2], 2)
+
+    shapes = ((1024, PC, STREAM, "non-temporal"), (1024, PC, THROUGH, "write-through"), (1024, PC, RESIDENT, "resident"),
+              (0, cc.CC_SCHEDULE_AUTO, cc.CC_CACHE_AUTO, "automatic"))
+    rows = []
+    for k in range(args.min_log2, args.max_log2 + 1):
+        shard = seeded_flat_shard(1 << k, args.R, seed=k)
+        row = {"log2": k}
+        for name, fn in (("adam", cc.cc_fused_adam_step), ("lamb", cc.cc_fused_lamb_step)):
+            for chunk, sched, policy, label in shapes:
+                set_shape(shard, chunk, sched, policy)
+                row[name + " " + label] = cold(shard, fn)
+        assert int(shard.flag.item()) == 0
+        shard.destroy()
+        del shard
+        torch.cuda.empty_cache()
+        rows.append(row)
+        print(json.dumps(row), flush=True)
+    if args.markdown:
+        cols = [name + " " + s[3] for name in ("adam", "lamb") for s in shapes]
+        with open(args.markdown, "w") as f:
+            f.write("| log2 N | " + " | ".join(cols) + " |\n|---|" + "---|" * len(cols) + "\n")
+            for r in rows:
+                f.write("| %d | " % r["log2"] + " | ".join("%.2f" % r[c] for c in cols) + " |\n")
+    return 0
+
+
 def mode_epilogue(argv) -> int:
     ap = argparse.ArgumentParser(prog="bench.py --mode epilogue")
     ap.add_argument("--steps", type=int, default=400)
@@ -288,4 +342,4 @@ def mode_small(argv) -> int:
 
 
 def main(mode: str, argv) -> int:
-    return {"sweep": mode_sweep, "rsweep": mode_rsweep, "epilogue": mode_epilogue, "small": mode_small}[mode](argv)
+    return {"sweep": mode_sweep, "rsweep": mode_rsweep, "cold": mode_cold, "epilogue": mode_epilogue, "small": mode_small}[mode](argv)
