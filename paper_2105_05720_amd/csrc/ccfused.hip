@@ -318,6 +318,7 @@ int cc_plan_create_ex(const cc_tensor *tensors, int32_t T, int32_t R, int32_t ch
             d.wd = x.weight_decay;
             d.first_chunk = (uint32_t)first;
             d.num_chunks = (uint32_t)((x.numel + (uint64_t)ce - 1) / (uint64_t)ce);
+            if (d.num_chunks > L.most_tensor_chunks) L.most_tensor_chunks = d.num_chunks;
             first += d.num_chunks;
         }
         std::vector<uint32_t> table;
@@ -675,8 +676,17 @@ int cc_fused_lamb_phase2(cc_plan *p, const cc_hparams *hp, const int32_t *flag, 
 
 int cc_fused_lamb_step(cc_plan *p, const cc_hparams *hp, int32_t *flag, void *stream)
 {
-    const int rc = cc_fused_lamb_phase1(p, hp, flag, stream);
+    StepScalars s;
+    int rc = check_step(p, hp, flag, Opt::Lamb, &s);
     if (rc) return rc;
+    if (norms_fold_into_phase2(p)) {
+        // two launches instead of three: nobody reads the sums between the phases here
+        hipStream_t st = (hipStream_t)stream;
+        launch_lamb_phase1(p, s, flag, st);
+        if ((rc = launched("lamb_phase1_kernel"))) return rc;
+        return lamb_phase2_with_norms(p, s, flag, st);
+    }
+    if ((rc = cc_fused_lamb_phase1(p, hp, flag, stream))) return rc;
     return cc_fused_lamb_phase2(p, hp, flag, stream);
 }
 

@@ -969,31 +969,58 @@ __global__ __launch_bounds__(BLOCK) void lamb_phase1_from_sum_kernel(const DevTe
     lamb_phase1_body<GradSum<Mem>, false, BLOCK>(tensors, chunks, s, partials, nullptr, nullptr);
 }
 
-// LAMB second level: one workgroup per tensor adds that tensor's chunk partials in a fixed order (four
-// independent strided partial sums per thread, then the block sum), so the result does not change between runs.
+// LAMB second level: a tensor's chunk partials are added in a fixed order, so the result does not change between runs
+// or between the launch shapes below.  The order is that of 1024 lanes: lane v adds the chunks v, v + 1024, ... into four
+// independent strided partial sums, the lanes of each 64-wide wave are added by a butterfly and the 16 wave totals one
+// after the other.  A workgroup of BLOCK < 1024 threads plays 1024 / BLOCK lanes per thread: its wave w stands for the
+// waves w, w + BLOCK / 64, ... of the wide one, so every addition has the same operands.
 constexpr int kNormBlock = 1024;
+template <int BLOCK>
+__device__ __forceinline__ void tensor_sums(const double *__restrict__ p, uint32_t n, double &sa, double &sb)
+{
+    constexpr int kRealWaves = BLOCK / 64, kWaves = kNormBlock / 64, kPlayed = kNormBlock / BLOCK;
+    static_assert(kNormBlock % BLOCK == 0 && BLOCK % 64 == 0, "a workgroup plays whole waves");
+    __shared__ double lds[2][kWaves];
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    __syncthreads();                     // a caller may use the function twice: the last call's reads are over
+#pragma unroll
+    for (int j = 0; j < kPlayed; ++j) {
+        const uint32_t played_wave = wave + j * kRealWaves;
+        double ta = 0.0, tb = 0.0;
+        if (played_wave * 64 < n) {      // a wave without chunks adds up zeros: the same +0.0, without the work
+            double a[4] = {0.0, 0.0, 0.0, 0.0}, b[4] = {0.0, 0.0, 0.0, 0.0};
+            uint32_t c = played_wave * 64 + lane;
+            for (; c + 3 * kNormBlock < n; c += 4 * kNormBlock) {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    a[k] += p[2 * (uint64_t)(c + k * kNormBlock)];
+                    b[k] += p[2 * (uint64_t)(c + k * kNormBlock) + 1];
+                }
+            }
+            for (int k = 0; c < n; c += kNormBlock, ++k) {
+                a[k] += p[2 * (uint64_t)c];
+                b[k] += p[2 * (uint64_t)c + 1];
+            }
+            ta = wave_sum((a[0] + a[1]) + (a[2] + a[3]));
+            tb = wave_sum((b[0] + b[1]) + (b[2] + b[3]));
+        }
+        if (lane == 0) { lds[0][played_wave] = ta; lds[1][played_wave] = tb; }
+    }
+    __syncthreads();
+    sa = lds[0][0];
+    sb = lds[1][0];
+#pragma unroll
+    for (int k = 1; k < kWaves; ++k) { sa += lds[0][k]; sb += lds[1][k]; }
+}
+
+// One workgroup per tensor.
 [[maybe_unused]] static __global__ __launch_bounds__(kNormBlock) void lamb_norms_kernel(const DevTensor *__restrict__ tensors,
                                                                 const double *__restrict__ partials,
                                                                 double *__restrict__ sums)
 {
     const DevTensor *t = tensors + blockIdx.x;
-    const uint32_t first = t->first_chunk, n = t->num_chunks;
-    const double *p = partials + 2 * (uint64_t)first;
-    double a[4] = {0.0, 0.0, 0.0, 0.0}, b[4] = {0.0, 0.0, 0.0, 0.0};
-    uint32_t c = threadIdx.x;
-    for (; c + 3 * kNormBlock < n; c += 4 * kNormBlock) {
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            a[k] += p[2 * (uint64_t)(c + k * kNormBlock)];
-            b[k] += p[2 * (uint64_t)(c + k * kNormBlock) + 1];
-        }
-    }
-    for (int k = 0; c < n; c += kNormBlock, ++k) {
-        a[k] += p[2 * (uint64_t)c];
-        b[k] += p[2 * (uint64_t)c + 1];
-    }
-    double sa = (a[0] + a[1]) + (a[2] + a[3]), sb = (b[0] + b[1]) + (b[2] + b[3]);
-    block_sum2<kNormBlock>(sa, sb);
+    double sa, sb;
+    tensor_sums<kNormBlock>(partials + 2 * (uint64_t)t->first_chunk, t->num_chunks, sa, sb);
     if (threadIdx.x == 0) {
         sums[2 * (uint64_t)blockIdx.x] = sa;
         sums[2 * (uint64_t)blockIdx.x + 1] = sb;
@@ -1056,6 +1083,31 @@ __global__ __launch_bounds__(BLOCK) void lamb_phase2_kernel(const DevTensor *__r
     if (*flag != 0) return;              // whole-step skip: w and w16 stay as they were
     const Where wh = locate(tensors, chunks, s.chunk_elems);
     const double sw = sums[2 * (uint64_t)wh.tensor], su = sums[2 * (uint64_t)wh.tensor + 1];
+    const float ratio = (sw > 0.0 && su > 0.0) ? (float)(__builtin_sqrt(sw) / __builtin_sqrt(su)) : 1.0f;
+    LambPhase2Op<EMIT16, Mem> op;
+    op.init(wh.t, wh.base, s, ratio);
+    stream_chunk<BLOCK>(op, wh.len);
+}
+
+// Phase 2 of a plan whose tensors have few chunks each, with the second level folded in: every workgroup adds up the
+// partials of its own tensor (the same additions in the same order as lamb_norms_kernel, so the same bits), which
+// costs 16 bytes per chunk of the tensor from the L2 and saves a launch.  The workgroup of a tensor's first chunk
+// also stores the sums, so that they can be read back as after the separate kernel.
+template <bool EMIT16, int BLOCK, class Mem = Streaming>
+__global__ __launch_bounds__(BLOCK) void lamb_phase2_with_norms_kernel(const DevTensor *__restrict__ tensors,
+                                                                       const Chunk *__restrict__ chunks, StepScalars s,
+                                                                       const double *__restrict__ partials,
+                                                                       double *__restrict__ sums,
+                                                                       const int32_t *__restrict__ flag)
+{
+    const Where wh = locate(tensors, chunks, s.chunk_elems);
+    double sw, su;
+    tensor_sums<BLOCK>(partials + 2 * (uint64_t)wh.t->first_chunk, wh.t->num_chunks, sw, su);
+    if (wh.base == 0 && threadIdx.x == 0) {
+        sums[2 * (uint64_t)wh.tensor] = sw;
+        sums[2 * (uint64_t)wh.tensor + 1] = su;
+    }
+    if (*flag != 0) return;              // whole-step skip: w and w16 stay as they were
     const float ratio = (sw > 0.0 && su > 0.0) ? (float)(__builtin_sqrt(sw) / __builtin_sqrt(su)) : 1.0f;
     LambPhase2Op<EMIT16, Mem> op;
     op.init(wh.t, wh.base, s, ratio);

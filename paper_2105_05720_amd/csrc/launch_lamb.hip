@@ -58,6 +58,14 @@ int lamb_phase2_impl(cc_plan *p, const StepScalars &s, const int32_t *flag, hipS
     return launched("lamb_phase2_kernel");
 }
 
+int lamb_phase2_with_norms(cc_plan *p, const StepScalars &s, const int32_t *flag, hipStream_t st)
+{
+    const Layout &L = p->lay();
+    const dim3 grid((unsigned)L.chunks);
+    BY_BLOCK_MEM(p, p->mem_lamb, hipLaunchKernelGGL((lamb_phase2_with_norms_kernel<true, BLK, MEM>), grid, dim3(BLK), 0, st, L.d_tensors, L.d_chunks, s, p->d_partials, p->d_sums, flag));
+    return launched("lamb_phase2_with_norms_kernel");
+}
+
 int lamb_norms(cc_plan *p, hipStream_t st)
 {
     hipLaunchKernelGGL(lamb_norms_kernel, dim3((unsigned)p->T), dim3(kNormBlock), 0, st, p->lay().d_tensors, p->d_partials, p->d_sums);

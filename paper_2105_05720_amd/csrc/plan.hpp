@@ -49,6 +49,7 @@ struct Layout {
     int block = kBigBlock;                       // threads per workgroup of the streaming kernels
     int64_t chunks = 0;
     uint32_t nfull = 0;                          // full chunks; the ordered table lists them first, short last chunks behind
+    uint32_t most_tensor_chunks = 0;             // chunks of the tensor that has the most
     std::vector<DevTensor> host_tensors;         // host mirror of the device descriptors (first_chunk / num_chunks of this chunking)
     DevTensor *d_tensors = nullptr;
     Chunk *d_chunks = nullptr;                   // tensor order
@@ -136,6 +137,18 @@ void launch_lamb_phase1(const cc_plan *p, const StepScalars &s, int32_t *flag, h
 void launch_lamb_phase1_from_sum(const cc_plan *p, const StepScalars &s, hipStream_t st);
 int lamb_phase2_impl(cc_plan *p, const StepScalars &s, const int32_t *flag, hipStream_t st, bool emit16);
 int lamb_norms(cc_plan *p, hipStream_t st);
+// Whether cc_fused_lamb_step lets every phase-2 workgroup add up its own tensor's partials instead of launching the
+// second level: one workgroup per chunk, and no tensor with more chunks than kFoldNormsMaxChunks.  A workgroup reads 16
+// bytes per chunk of its tensor, so the extra L2 traffic grows with the square of a tensor's chunks.  One flat tensor,
+// R = 8, us per step folded / three launches: 10.5 / 11.8 at one chunk, 9.1 / 10.7 at 128, 10.1 / 10.9 at 256, but
+// 12.3 / 11.9 at 512 and 17.8 / 14.3 at 1024.
+constexpr uint32_t kFoldNormsMaxChunks = 256;
+inline bool norms_fold_into_phase2(const cc_plan *p)
+{
+    const Layout &L = p->lay();
+    return !p->ordered && L.block == kSmallBlock && L.chunks > 0 && L.most_tensor_chunks <= kFoldNormsMaxChunks;
+}
+int lamb_phase2_with_norms(cc_plan *p, const StepScalars &s, const int32_t *flag, hipStream_t st);
 void launch_reduce(const cc_plan *p, const StepScalars &s, int32_t *flag, hipStream_t st);
 void launch_reduce_half(const cc_plan *p, const StepScalars &s, int32_t *flag, hipStream_t st);
 void launch_adam_from_sum(const cc_plan *p, const StepScalars &s, const int32_t *flag, hipStream_t st, int mode, bool sum16);

@@ -216,6 +216,48 @@ def test_lamb_norms_match_oracle_and_phases_compose():
     shard.destroy()
 
 
+def _two_phase_lamb_step(plan, hp, flag, stream=None):
+    cc.cc_fused_lamb_phase1(plan, hp, flag, stream)
+    cc.cc_fused_lamb_phase2(plan, hp, flag, stream)
+
+
+@pytest.mark.parametrize("numels", [[256 * 1024, 200 * 1024 + 5, 0, 65 * 1024, 64 * 1024 + 1, 7], [256 * 1024 + 1, 3000]])
+def test_lamb_step_call_and_its_two_phase_calls_give_the_same_bits(numels):
+    """cc_fused_lamb_step lets the phase-2 workgroups add up their own tensor's partials when no tensor has more than
+    256 chunks (first list: 256, 201, 0, 65, 65 and 1 chunks; second list: 257, the three-launch way); the two phase
+    calls always launch the per-tensor kernel.  Sums and state must agree bit for bit, and with the oracle."""
+    outs = []
+    for fn in (cc.cc_fused_lamb_step, _two_phase_lamb_step):
+        shard = Shard(numels, [0.01, 0.0, 0.01, 0.01, 0.0, 0.01][:len(numels)], 4, chunk_elems=1024, align_elems=8)
+        seeded_state(shard, 21)
+        ost = OracleState(shard, range(len(numels)))
+        sums = []
+        for t in (1, 2):
+            seeded_grads(shard, 210 + t, 1e-2)
+            ghp, ohp = hyper_pair(step=t)
+            ots = ost.tensors(shard)
+            oracle.lamb_step(ots, ohp)
+            plan = shard.plans[shard.cur]
+            shard.run(fn, ghp)
+            got = cc.cc_lamb_norms_read(plan, len(numels))
+            for (sw, su), o, n in zip(got, ots, numels):
+                if n == 0:
+                    assert sw == 0.0 and su == 0.0
+                else:
+                    assert np.sqrt(sw) == pytest.approx(o.norms[0], rel=1e-6) and np.sqrt(su) == pytest.approx(o.norms[1], rel=1e-6)
+            sums.append(np.asarray(got))
+            assert int(shard.flag.item()) == 0
+            shard.commit()
+            ost.adopt(ots)
+            compare_committed(shard, ost, "lamb step %d" % t)
+        outs.append((sums, shard.w[shard.cur].cpu(), shard.m[shard.cur].cpu(), shard.v[shard.cur].cpu(),
+                     shard.w16[shard.cur].view(torch.int16).cpu()))
+        shard.destroy()
+    (sa, *a), (sb, *b) = outs
+    assert all(np.array_equal(x.view(np.int64), y.view(np.int64)) for x, y in zip(sa, sb)), "the two ways add in different orders"
+    assert _same(a, b)
+
+
 # ---------------------------------------------------------------------------- invariances on the GPU side
 
 def _gpu_adam_bits(numels, R, chunk, fn=None, flat=False, hkw=None, seed=11):
