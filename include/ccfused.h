@@ -168,8 +168,9 @@ int cc_plan_layout(const cc_plan *plan, int32_t *chunk_elems, int32_t *block_thr
  * fits the 256 MB Infinity Cache finds its inputs on chip in the next step.  WRITE_THROUGH keeps the non-temporal loads
  * and writes the stores through, for shards of which one launch's output still about fits that cache.  The last two
  * exist for 128-thread workgroups (chunks below 4096 elements) and are ignored otherwise.  Results do not depend on
- * the policy.  AUTO (default): RESIDENT while the step's buffers total less than 200 MiB (4-20 % faster than STREAMING
- * between 2^18 and 2^22 elements in the size sweep, equal below); else WRITE_THROUGH while a launch stores less than
+ * the policy.  AUTO (default): STREAMING while the step's buffers total less than 4 MiB (1-6 % faster there); else
+ * RESIDENT while they total less than 200 MiB (4-24 % faster than STREAMING between 2^18 and 2^22 elements in the size
+ * sweep); else WRITE_THROUGH while a launch stores less than
  * 288 MiB (the Adam step stores 14 bytes per element: up to 20.5 Mi elements, 8-12 % faster at 2^23 and 2^24; LAMB's
  * sweeps store 8 and 6: up to 36 Mi elements, and cc_plan_layout reports the Adam step's policy); else STREAMING.
  * cc_plan_autotune tries all three.

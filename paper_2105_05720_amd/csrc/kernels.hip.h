@@ -278,16 +278,23 @@ struct FlagCount {
             }
         }
     }
-    // Before the wave's stores: the last arrival of the launch tidies the counters and starts clearing the flag.
+    // Before the wave's stores: the last arrival of the launch tidies the counters and starts clearing the flag.  Every
+    // lane of the wave calls this.  The slots a small launch did not use are moved on by all 64 lanes at once, behind
+    // the flag's exchange: one lane doing it slot by slot, in front of the exchange, cost a launch of one workgroup 2 us.
     __device__ __forceinline__ void top_level(FlagScratch *fs, int32_t *flag)
     {
         if (counting_lane() && slot_last) {
             launch_last = (uint32_t)tprev == used - 1;
             if (launch_last) {
                 atomicExch(&fs->top.word, 0ull);
-                for (uint32_t k = used; k < kFlagSlots; ++k) atomicExch(&fs->slot[k].word, (unsigned long long)tag() << 32);
                 flag_before = __hip_atomic_exchange(flag, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
+        }
+        if (__builtin_amdgcn_ballot_w64(launch_last) != 0ull) {            // uniform: this wave holds the last arrival
+            const uint32_t first_unused = (uint32_t)__builtin_amdgcn_readfirstlane((int)used);
+            const uint32_t next_tag = (uint32_t)__builtin_amdgcn_readfirstlane((int)tag());
+            for (uint32_t k = first_unused + (threadIdx.x & 63u); k < kFlagSlots; k += 64u)
+                atomicExch(&fs->slot[k].word, (unsigned long long)next_tag << 32);
         }
     }
     // After the wave's stores have been issued: reports.

@@ -22,10 +22,11 @@ constexpr int kBigBlock = 512, kSmallBlock = 128;
 constexpr int kOrderedMaxF32Slices = 8;           // fp32 slices: the ordered schedule wins up to 8 (config-2 list: 3.18 against 3.41 ms), at 16 two chunks spill
 constexpr int64_t kOrderedMinChunksPerCu = 8;    // below this many chunks per compute unit a plan keeps one workgroup per chunk
 // AUTO cache policy: plain loads and write-through stores instead of non-temporal accesses while the step's buffers (R
-// gradient slices, both copies of w, m, v and of the fp16 weights) total less than this, i.e. fit the 256 MB Infinity
-// Cache.  Size sweep at R = 8, us per step: 6.2 against 7.9 at 2^20 elements (44 MB), 14.9 against 15.8 at 2^21 (88 MB),
-// 27.6 against 29.6 at 2^22 (176 MB), but 68.1 against 60.2 at 2^23 (352 MB); below 2^18 the two are within 0.2 us.
-constexpr uint64_t kResidentMaxBytes = 200ull << 20;
+// gradient slices, both copies of w, m, v and of the fp16 weights) total between these bounds, i.e. fit the 256 MB
+// Infinity Cache.  Size sweep at R = 8, us per step: 6.2 against 7.9 at 2^20 elements (44 MB), 14.9 against 15.8 at 2^21
+// (88 MB), 27.6 against 29.6 at 2^22 (176 MB), but 68.1 against 60.2 at 2^23 (352 MB).  Below 2^17 elements the
+// non-temporal accesses are the faster ones by 1-6 % (LAMB at 2^14: 7.7 against 8.0 us), hence the lower bound.
+constexpr uint64_t kResidentMinBytes = 4ull << 20, kResidentMaxBytes = 200ull << 20;
 // ... and from there on non-temporal loads with write-through stores while one kernel stores less than this (see
 // WriteThrough): what a launch writes then about fits the Infinity Cache.  Fused Adam (14 B stored per element) at
 // R = 8: 141 against 147 us at 20 Mi elements, 160 against 157 us at 22 Mi; fused LAMB (8 B in its first sweep, 6 B in
@@ -34,6 +35,7 @@ constexpr uint64_t kWriteThroughMaxStoreBytes = 288ull << 20;
 constexpr uint32_t kAdamStoreBytes = 14, kLambStoreBytes = 8;      // per element: w', m', v', w16 / m', v'
 inline int32_t auto_cache_policy(uint64_t footprint, uint64_t stored)
 {
+    if (footprint < kResidentMinBytes) return CC_CACHE_STREAMING;
     return footprint < kResidentMaxBytes ? CC_CACHE_RESIDENT : stored < kWriteThroughMaxStoreBytes ? CC_CACHE_WRITE_THROUGH : CC_CACHE_STREAMING;
 }
 

@@ -104,6 +104,9 @@ def test_auto_policy_and_layout_rules():
     big = Shard([1 << 23], [0.0], 8, align_elems=8, unfused=False)                      # 352 MB: streams in, writes through
     assert cc.cc_plan_layout(big.plans[0]) == (1024, 128, cc.CC_CACHE_WRITE_THROUGH)
     big.destroy()
+    tiny = Shard([1 << 16], [0.0], 8, align_elems=8, unfused=False)                     # 2.75 MB: launch-bound, streams
+    assert cc.cc_plan_layout(tiny.plans[0]) == (1024, 128, cc.CC_CACHE_STREAMING)
+    tiny.destroy()
     for mi, want in ((20, cc.CC_CACHE_WRITE_THROUGH), (21, cc.CC_CACHE_STREAMING)):     # 14 B stored per element against 288 MiB
         edge = Shard([mi << 20], [0.0], 2, align_elems=8, unfused=False)
         assert cc.cc_plan_layout(edge.plans[0]) == (1024, 128, want)
