@@ -482,9 +482,11 @@ __device__ __forceinline__ void ordered_stream(Op &opa, Op &opb, Bind bind, uint
 #pragma unroll
         for (int g = 0; g < GROUPS; ++g) opa.load(xa[g], g * kGroup + lane_e);
         while (true) {
-            wb = bind(opb, n < nfull ? n : e);     // past the full chunks: reload the own chunk, the values are not used
+            if (n < nfull) {                       // past the full chunks there is nothing to fetch ahead
+                wb = bind(opb, n);
 #pragma unroll
-            for (int g = 0; g < GROUPS; ++g) opb.load(xb[g], g * kGroup + lane_e);
+                for (int g = 0; g < GROUPS; ++g) opb.load(xb[g], g * kGroup + lane_e);
+            }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int g = 0; g < GROUPS; ++g) { opa.compute(xa[g]); opa.store(xa[g], g * kGroup + lane_e); }
@@ -492,9 +494,11 @@ __device__ __forceinline__ void ordered_stream(Op &opa, Op &opb, Bind bind, uint
             __builtin_amdgcn_sched_barrier(0);
             const uint32_t n2 = en.next();
             if (n >= nfull) { e = n; n = n2; break; }
-            wa = bind(opa, n2 < nfull ? n2 : n);
+            if (n2 < nfull) {
+                wa = bind(opa, n2);
 #pragma unroll
-            for (int g = 0; g < GROUPS; ++g) opa.load(xa[g], g * kGroup + lane_e);
+                for (int g = 0; g < GROUPS; ++g) opa.load(xa[g], g * kGroup + lane_e);
+            }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int g = 0; g < GROUPS; ++g) { opb.compute(xb[g]); opb.store(xb[g], g * kGroup + lane_e); }
