@@ -29,10 +29,10 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # HBM bytes per launch of the headline kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by what
 # the same counter reads for the plain copy kernel: default chunk size and schedule, fp16 slices, scattered list only.
 # These are constants copied from the kept profiles, not measured by this run.
-MEASURED_TRAFFIC = {2: (9.4497e9 + 4.7096e9, "profiles/fused_adam_config2.md"),
-                    3: (1.3499e10 + 4.7133e9, "profiles/fused_lamb_config3.md"),
-                    4: (4.3673e10 + 2.1818e10, "profiles/fused_adam_config4.md"),
-                    5: (4.1657e10 + 1.4573e10, "profiles/fused_lamb_config5.md")}
+MEASURED_TRAFFIC = {2: (9.4217e9 + 4.7096e9, "profiles/fused_adam_config2.md"),
+                    3: (1.3462e10 + 4.7132e9, "profiles/fused_lamb_config3.md"),
+                    4: (4.3644e10 + 2.1818e10, "profiles/fused_adam_config4.md"),
+                    5: (4.1621e10 + 1.4573e10, "profiles/fused_lamb_config5.md")}
 
 WORKLOAD_NAMES = {1: "one flat tensor", 2: "BERT-Large parameter list", 3: "BERT-Large parameter list",
                   4: "GPT-2 1.5B parameter list", 5: "1/8 shard of an 8.3B transformer"}
