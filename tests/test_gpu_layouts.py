@@ -73,6 +73,31 @@ def test_resident_policy_every_kind_of_R_and_fp32_slices(R):
         assert all(torch.equal(x, y) and torch.equal(x, z) for x, y, z in zip(a, b, c))
 
 
+def test_in_place_guard_mode_under_every_cache_policy():
+    """skip_mode 1 reads and writes the same buffers; the written-through stores go through inline assembly, so the guard's
+    "keep the input" case and the ordinary case are checked against the oracle under each policy, with an inf, a NaN made
+    of opposite infinities and a NaN in a ragged tail planted in the first step, and the policies must agree bit for bit."""
+    outs = []
+    for policy in (cc.CC_CACHE_STREAMING, cc.CC_CACHE_RESIDENT, cc.CC_CACHE_WRITE_THROUGH):
+        numels = [1024 * 9 + 1023, 100, 4096]
+        sh = Shard(numels, [0.01, 0.0, 0.01], 4, in_place=True, align_elems=8, chunk_elems=1024, cache_policy=policy)
+        assert cc.cc_plan_layout(sh.plans[0]) == (1024, 128, policy)
+        seeded_state(sh, 6)
+        ost = OracleState(sh, range(3))
+
+        def fill(i):
+            seeded_grads(sh, 60 + i, 1e-2)
+            if i == 0:
+                for r, t, e, bits in ((0, 0, 4100, 0x7C00), (3, 0, 4100, 0xFC00), (2, 0, 1024 * 9 + 1000, 0x7C00), (1, 1, 99, 0x7D55)):
+                    sh.grad_of(r, t).view(torch.int16)[e] = bits - 0x10000 if bits >= 0x8000 else bits
+        hps = [hyper_pair(step=1, skip_mode=1), hyper_pair(step=2, skip_mode=1), hyper_pair(step=3, skip_mode=1, adam_mode=0, grad_average=1)]
+        run_steps(sh, ost, cc.cc_fused_adam_step, oracle.adam_step, hps, "guard, policy %d" % policy, fill, expect_flags=[1, 0, 0])
+        outs.append(bits_of(sh))
+        sh.destroy()
+    for other in outs[1:]:
+        assert all(torch.equal(a, b) for a, b in zip(outs[0], other))
+
+
 def test_single_tensor_plan_resident_and_streaming():
     """One tensor: the table-free kernel, both policies, against the oracle (2^17 + a ragged end)."""
     for policy in (cc.CC_CACHE_RESIDENT, cc.CC_CACHE_STREAMING, cc.CC_CACHE_WRITE_THROUGH):
