@@ -232,7 +232,7 @@ int cc_fused_adam_step_static(const cc_tensor *tensor, int32_t R, const cc_hpara
  * writes w' = w - lr ratio u and w16.  On overflow phase 2 leaves w_out and w16_out untouched.
  * cc_fused_lamb_step = phase 1 then phase 2.  The two phases are exported separately so that a
  * cross-rank sum of the per-tensor norms can be placed between them.  The single call gives the same bits in two
- * launches instead of three when no tensor has more than 256 chunks: the workgroups of phase 2 then add up their own
+ * launches instead of three when no tensor has more than 512 chunks: the workgroups of phase 2 then add up their own
  * tensor's partial sums (same additions, same order) instead of a per-tensor launch between the phases.
  */
 int cc_fused_lamb_step(cc_plan *plan, const cc_hparams *hp, int32_t *d_overflow_flag, void *hip_stream);

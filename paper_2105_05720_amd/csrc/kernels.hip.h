@@ -994,6 +994,23 @@ __device__ __forceinline__ void tensor_sums(const double *__restrict__ p, uint32
     __shared__ double lds[2][kWaves];
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     __syncthreads();                     // a caller may use the function twice: the last call's reads are over
+    if (n <= (uint32_t)kNormBlock) {
+        // At most one chunk per lane: the lane's four strided sums are that chunk's value and zeros, i.e. the value
+        // itself, so all loads can be issued at once (a lane that plays eight would otherwise wait eight times).
+        double ta[kPlayed], tb[kPlayed];
+#pragma unroll
+        for (int j = 0; j < kPlayed; ++j) {
+            const uint32_t c = (wave + j * kRealWaves) * 64 + lane;
+            ta[j] = c < n ? p[2 * (uint64_t)c] : 0.0;
+            tb[j] = c < n ? p[2 * (uint64_t)c + 1] : 0.0;
+        }
+#pragma unroll
+        for (int j = 0; j < kPlayed; ++j) {
+            const uint32_t played_wave = wave + j * kRealWaves;
+            if (played_wave * 64 < n) { ta[j] = wave_sum(ta[j]); tb[j] = wave_sum(tb[j]); }
+            if (lane == 0) { lds[0][played_wave] = ta[j]; lds[1][played_wave] = tb[j]; }
+        }
+    } else
 #pragma unroll
     for (int j = 0; j < kPlayed; ++j) {
         const uint32_t played_wave = wave + j * kRealWaves;

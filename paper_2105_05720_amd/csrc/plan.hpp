@@ -141,10 +141,10 @@ int lamb_phase2_impl(cc_plan *p, const StepScalars &s, const int32_t *flag, hipS
 int lamb_norms(cc_plan *p, hipStream_t st);
 // Whether cc_fused_lamb_step lets every phase-2 workgroup add up its own tensor's partials instead of launching the
 // second level: one workgroup per chunk, and no tensor with more chunks than kFoldNormsMaxChunks.  A workgroup reads 16
-// bytes per chunk of its tensor, so the extra L2 traffic grows with the square of a tensor's chunks.  One flat tensor,
-// R = 8, us per step folded / three launches: 10.5 / 11.8 at one chunk, 9.1 / 10.7 at 128, 10.1 / 10.9 at 256, but
-// 12.3 / 11.9 at 512 and 17.8 / 14.3 at 1024.
-constexpr uint32_t kFoldNormsMaxChunks = 256;
+// bytes per chunk of its tensor, so the extra traffic grows with the square of a tensor's chunks.  One flat tensor,
+// R = 8, us per step folded / three launches: 7.1 / 8.9 at one chunk, 9.2 / 10.7 at 128, 9.6 / 10.9 at 256, 11.4 / 11.6
+// at 512, but 16.5 / 14.3 at 1024.
+constexpr uint32_t kFoldNormsMaxChunks = 512;
 inline bool norms_fold_into_phase2(const cc_plan *p)
 {
     const Layout &L = p->lay();

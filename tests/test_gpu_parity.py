@@ -221,10 +221,10 @@ def _two_phase_lamb_step(plan, hp, flag, stream=None):
     cc.cc_fused_lamb_phase2(plan, hp, flag, stream)
 
 
-@pytest.mark.parametrize("numels", [[256 * 1024, 200 * 1024 + 5, 0, 65 * 1024, 64 * 1024 + 1, 7], [256 * 1024 + 1, 3000]])
+@pytest.mark.parametrize("numels", [[1 << 19, 300 * 1024 + 5, 0, 65 * 1024, 64 * 1024 + 1, 7], [512 * 1024 + 1, 3000]])
 def test_lamb_step_call_and_its_two_phase_calls_give_the_same_bits(numels):
     """cc_fused_lamb_step lets the phase-2 workgroups add up their own tensor's partials when no tensor has more than
-    256 chunks (first list: 256, 201, 0, 65, 65 and 1 chunks; second list: 257, the three-launch way); the two phase
+    512 chunks (first list: 512, 301, 0, 65, 65 and 1 chunks; second list: 513, the three-launch way); the two phase
     calls always launch the per-tensor kernel.  Sums and state must agree bit for bit, and with the oracle."""
     outs = []
     for fn in (cc.cc_fused_lamb_step, _two_phase_lamb_step):
