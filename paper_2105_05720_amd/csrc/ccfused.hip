@@ -509,15 +509,15 @@ int check_hparams(const cc_hparams *hp, const void *flag, Opt opt, int32_t R, bo
         return fail(CC_ERR_ALIAS, "skip_mode 0 (whole-step skip) needs out buffers distinct from the in buffers");
     const double b1 = hp->beta1, b2 = hp->beta2;
     const double c1 = 1.0 - std::pow(b1, (double)hp->step), c2 = 1.0 - std::pow(b2, (double)hp->step);
-    s->beta1 = hp->beta1;
-    s->beta2 = hp->beta2;
-    s->omb1 = (float)(1.0 - b1);
-    s->omb2 = (float)(1.0 - b2);
+    s->beta1 = b1;
+    s->beta2 = b2;
+    s->omb1 = 1.0 - b1;
+    s->omb2 = 1.0 - b2;
     s->rc1 = (float)(1.0 / c1);
     s->rc2 = (float)(1.0 / c2);
     s->eps = hp->eps;
     s->lr = hp->lr;
-    s->inv_div = (float)(1.0 / ((double)hp->loss_scale * (hp->grad_average ? (double)R : 1.0)));
+    s->inv_div = 1.0 / ((double)hp->loss_scale * (hp->grad_average ? (double)R : 1.0));
     s->chunk_elems = (uint32_t)chunk_elems;
     return CC_OK;
 }

@@ -61,11 +61,11 @@ struct Chunk {
 
 // Scalars of one step, precomputed on the host in double and rounded once.
 struct StepScalars {
-    float beta1, beta2;
-    float omb1, omb2;         // 1 - beta
+    double inv_div;           // 1 / (loss_scale * (average ? R : 1))
+    double beta1, beta2;      // the interface's fp32 values, promoted
+    double omb1, omb2;        // 1 - beta, exact in double
     float rc1, rc2;           // 1 / (1 - beta^t)
     float eps, lr;
-    float inv_div;            // 1 / (loss_scale * (average ? R : 1))
     uint32_t chunk_elems;
 };
 
@@ -73,14 +73,19 @@ enum : int { kModeGuard = 1, kModeL2 = 2 };
 
 __device__ __forceinline__ bool not_finite(float x) { return !(__builtin_fabsf(x) <= 3.402823466e+38f); }
 
-// Moments of one element from the reduced sum S (Fig. 4a: the m and v updates).
+// Moments of one element from the reduced sum S (Fig. 4a: the m and v updates), each formed in double from the fp32
+// inputs and rounded to fp32 once, so that the stored moments are the correctly rounded values of their definitions
+// (up to double rounding).  In fp32 the terms would be rounded one by one, and where they cancel (the two terms of
+// m', or S / (loss_scale D) against wd w in L2 mode) the result carries those roundings at full size: random cases
+// put a few elements at 1.3 x the parity bound that way.  Eight double-precision operations per element, which
+// neither the HBM-bound nor the launch-bound kernels notice.
 template <int MODE>
 __device__ __forceinline__ void moments(float S, float w, float wd, const StepScalars &s, float &m, float &v)
 {
-    float g = S * s.inv_div;
-    if (MODE & kModeL2) g = __builtin_fmaf(wd, w, g);
-    m = __builtin_fmaf(s.beta1, m, s.omb1 * g);
-    v = __builtin_fmaf(s.beta2, v, (s.omb2 * g) * g);
+    double g = (double)S * s.inv_div;
+    if (MODE & kModeL2) g = __builtin_fma((double)wd, (double)w, g);
+    m = (float)__builtin_fma(s.beta1, (double)m, s.omb1 * g);
+    v = (float)__builtin_fma(s.beta2, (double)v, (s.omb2 * g) * g);
 }
 
 // Update direction u from the new moments (Fig. 4a: bias corrections and the quotient), plus decoupled decay.

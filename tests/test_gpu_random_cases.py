@@ -79,3 +79,13 @@ def test_random_case_ordered_schedule(seed):
     c["chunk"] = 4096
     c["numels"] = [n * int(rng.choice([1, 1, 3, 8])) for n in c["numels"]]
     run_case(seed, c, rng, schedule=cc.CC_SCHEDULE_ORDERED, workgroups=int(rng.choice([1, 2, 3, 5, 8, 13, 32, 100, 0])))
+
+
+@pytest.mark.parametrize("seed", range(30))
+def test_random_case_written_through_stores(seed):
+    """The same kind of draw on the 128-thread kernels under the two cache policies whose vector stores are written in
+    assembly (chunks of 1024 or 2048 elements; small tests would otherwise all run under the non-temporal policy)."""
+    rng = np.random.default_rng(9000 + seed)
+    c = draw_case(rng)
+    c["chunk"] = int(rng.choice([1024, 2048]))
+    run_case(seed, c, rng, cache_policy=int(rng.choice([cc.CC_CACHE_RESIDENT, cc.CC_CACHE_WRITE_THROUGH])))
