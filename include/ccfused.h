@@ -198,8 +198,9 @@ int cc_plan_info(const cc_plan *plan, uint64_t *numel, int64_t *chunks, uint64_t
 /* ---- fused steps (one pass over HBM per sweep) ---- */
 
 /*
- * Adam (Fig. 4a with the schedule of Fig. 4b).  Per element i of every tensor (S, gh, m' and v' are formed in double and
- * rounded to fp32 once each; u and w' in fp32):
+ * Adam (Fig. 4a with the schedule of Fig. 4b).  Per element i of every tensor (the slices are added in double and S is
+ * rounded to fp32; gh, m' and v' are formed in double from S, m and v, and m' and v' rounded to fp32 once each; u and w'
+ * are computed in fp32 from the rounded moments):
  *   S = g_0[i] + g_1[i] + ... + g_{R-1}[i]   (fixed rank order)     gh = S / (loss_scale * (avg ? R : 1))
  *   m' = beta1 m + (1-beta1) gh      v' = beta2 v + (1-beta2) gh^2
  *   u  = (m'/(1-beta1^t)) / (sqrt(v'/(1-beta2^t)) + eps) + wd w     w' = w - lr u     w16 = fp16(w')
