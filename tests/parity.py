@@ -82,8 +82,10 @@ def all_inputs_finite(shard: Shard) -> bool:
 
 def run_steps(shard: Shard, ost: OracleState, gpu_fn: Callable, oracle_fn: Callable, hps, label: str,
               fill_grads: Callable[[int], None], expect_flags: Optional[Sequence[int]] = None,
-              check_untouched: bool = True):
+              check_untouched: bool = True, same_start: bool = False):
     """hps: one (gpu hyper, oracle hyper) pair per call.  fill_grads(i) writes the i-th call's gradients.
+    same_start: before every call the oracle takes over the GPU's committed fp32 state, so that each step is compared
+    from identical inputs; otherwise both sides follow their own trajectory and the differences of earlier steps stay in.
 
     When the oracle holds only part of the tensor list, every non-finite input must sit in a tensor it holds
     (the tests arrange that and confirm it with all_inputs_finite on the other calls).
@@ -92,6 +94,9 @@ def run_steps(shard: Shard, ost: OracleState, gpu_fn: Callable, oracle_fn: Calla
     for i, (ghp, ohp) in enumerate(hps):
         fill_grads(i)
         torch.cuda.synchronize()
+        if same_start:
+            for k in ost.which:
+                ost.w[k], ost.m[k], ost.v[k] = (to_np_f32(x).copy() for x in (shard.w_of(k), shard.m_of(k), shard.v_of(k)))
         ots = ost.tensors(shard)
         oflag = oracle_fn(ots, ohp, threads=THREADS)
         before = shard.cur

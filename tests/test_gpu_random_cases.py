@@ -48,7 +48,7 @@ def draw_case(rng):
     return case
 
 
-def run_case(seed, c, rng, **shard_kw):
+def run_case(seed, c, rng, same_start=False, steps=2, **shard_kw):
     shard = Shard(c["numels"], c["wds"], c["R"], chunk_elems=c["chunk"], in_place=c["in_place"], align_elems=8,
                   grad_dtype=torch.float32 if c["f32"] else torch.float16, **shard_kw)
     seeded_state(shard, seed)
@@ -58,9 +58,10 @@ def run_case(seed, c, rng, **shard_kw):
     else:
         gpu_fn, ofn = (cc.cc_unfused_adam_step if c["unfused"] else cc.cc_fused_adam_step), oracle.adam_step
     t0 = int(rng.integers(1, 2000))
-    hps = [hyper_pair(step=t0 + i, **c["hp"]) for i in range(2)]
+    hps = [hyper_pair(step=t0 + i, **c["hp"]) for i in range(steps)]
     run_steps(shard, ost, gpu_fn, ofn, hps, "random case %d %r" % (seed, c),
-              lambda i: seeded_grads(shard, seed * 10 + i, c["gstd"] * c["hp"]["loss_scale"] if c["hp"]["loss_scale"] <= 128 else c["gstd"]))
+              lambda i: seeded_grads(shard, seed * 10 + i, c["gstd"] * c["hp"]["loss_scale"] if c["hp"]["loss_scale"] <= 128 else c["gstd"]),
+              same_start=same_start)
     shard.destroy()
 
 
@@ -89,3 +90,22 @@ def test_random_case_written_through_stores(seed):
     c = draw_case(rng)
     c["chunk"] = int(rng.choice([1024, 2048]))
     run_case(seed, c, rng, cache_policy=int(rng.choice([cc.CC_CACHE_RESIDENT, cc.CC_CACHE_WRITE_THROUGH])))
+
+
+@pytest.mark.parametrize("seed", range(40, 130))
+def test_random_case_step_by_step(seed):
+    """Three steps per draw, each taken by the oracle from the state the GPU committed, so that every single step is
+    compared from identical inputs (the tests above let both sides run on from their own results, which also lets the
+    admissible error of one step move the next).  The three kinds of launch above take turns."""
+    kind = seed % 3
+    rng = np.random.default_rng((1000, 5000, 9000)[kind] + seed)
+    c = draw_case(rng)
+    kw = {}
+    if kind == 1:
+        c["chunk"] = 4096
+        c["numels"] = [n * int(rng.choice([1, 1, 3, 8])) for n in c["numels"]]
+        kw = dict(schedule=cc.CC_SCHEDULE_ORDERED, workgroups=int(rng.choice([1, 2, 3, 5, 8, 13, 32, 100, 0])))
+    elif kind == 2:
+        c["chunk"] = int(rng.choice([1024, 2048]))
+        kw = dict(cache_policy=int(rng.choice([cc.CC_CACHE_RESIDENT, cc.CC_CACHE_WRITE_THROUGH])))
+    run_case(seed, c, rng, same_start=True, steps=3, **kw)
