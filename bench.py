@@ -10,7 +10,7 @@ pipelines, a plain copy kernel (the practical HBM ceiling) and the CPU oracle on
 printed.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--chunk-elems N] [--no-extras]
-    python bench.py --mode sweep|rsweep|cold|epilogue|small   (measurement programs behind profiles/*.md, see bench_sweeps.py)
+    python bench.py --mode sweep|rsweep|cold|sliced|epilogue|small   (measurement programs behind profiles/*.md, see bench_sweeps.py)
 """
 from __future__ import annotations
 
@@ -148,7 +148,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--mode", choices=("step", "sweep", "rsweep", "cold", "epilogue", "small"), default="step",
+    ap.add_argument("--mode", choices=("step", "sweep", "rsweep", "cold", "sliced", "epilogue", "small"), default="step",
                     help="step: the benchmark line (default); the others are the measurement programs of bench_sweeps.py")
     ap.add_argument("--config", type=int, default=2, help="workload configuration 1..5 (default 2, the metric's)")
     ap.add_argument("--chunk-elems", type=int, default=0)

@@ -4,6 +4,7 @@
             standalone experiment, Section 6.1.1 / Fig. 7), with the launch shape tuned per size
   rsweep    the same for R in {1, 2, 4, 8, 16} and fp16 / fp32 gradient slices at 2^20, 2^24 and 2^28 elements
   cold      single fused steps with the caches evicted before each one, per cache policy (2^18 .. 2^26 elements)
+  sliced    the BERT-Large parameter list with every tensor cut into 8, 64 or 256 slices: one rank's share
   epilogue  the fused model-parallel epilogue against its unfused pipeline at the sizes of the paper's standalone
             model-parallel experiment (Section 6.2.1)
   small     where the time of a launch-bound 2^20-element step goes: the step's memory pattern with parts taken away
@@ -240,6 +241,49 @@ def mode_cold(argv) -> int:
     return 0
 
 
+def mode_sliced(argv) -> int:
+    """Every tensor of the BERT-Large list cut into `ranks` slices, one rank's share (Section 5.2, "Sliced Tensor": what a
+    rank updates after the fused schedule's reduce-scatter): 398 tensors per rank, most of them a handful of elements."""
+    from paper_2105_05720_amd import workloads as W
+    ap = argparse.ArgumentParser(prog="bench.py --mode sliced")
+    ap.add_argument("--ranks", type=str, default="8,64,256")
+    ap.add_argument("--R", type=int, default=8)
+    ap.add_argument("--markdown", type=str, default="")
+    args = ap.parse_args(argv)
+    specs = W.bert_large_list()
+    rows = []
+    for ranks in (int(x) for x in args.ranks.split(",")):
+        numels = [(s.numel + ranks - 1) // ranks for s in specs]
+        shard = Shard(numels, [0.01 if s.decays else 0.0 for s in specs], args.R, align_elems=1024, unfused=True)
+        g = torch.Generator(device="cuda")
+        g.manual_seed(ranks)
+        shard.w[0].normal_(0.0, 0.02, generator=g)
+        for arena in shard.grads:
+            arena.copy_(torch.empty(arena.numel(), device="cuda").normal_(0.0, 1e-3, generator=g))
+        n = sum(numels)
+        chunk, block, policy = cc.cc_plan_layout(shard.plans[0])
+        row = {"ranks": ranks, "numel": n, "tensors": len(numels), "chunks": cc.cc_plan_info(shard.plans[0])[1],
+               "chunk_elems": chunk, "cache_policy": policy}
+        for name, fn, bpp in paths(args.R, 2):
+            us = time_step(shard, fn, 2000 if n < (1 << 23) else 400)
+            row[name] = {"us": round(us, 2), "GB/s": round(bpp * n / us / 1e3, 1)}
+        shard.destroy()
+        del shard
+        torch.cuda.empty_cache()
+        rows.append(row)
+        print(json.dumps(row), flush=True)
+    if args.markdown:
+        with open(args.markdown, "w") as f:
+            f.write("| ranks | elements per rank | tensors | chunks | fused Adam us | GB/s | % of 8 TB/s | unfused Adam us | speed-up | fused LAMB us | GB/s | unfused LAMB us | speed-up |\n"
+                    "|---|---|---|---|---|---|---|---|---|---|---|---|---|\n")
+            for r in rows:
+                a, ua, l, ul = r["fused_adam"], r["unfused_adam"], r["fused_lamb"], r["unfused_lamb"]
+                f.write("| %d | %d | %d | %d | %.2f | %.0f | %.1f | %.2f | %.2fx | %.2f | %.0f | %.2f | %.2fx |\n" % (
+                    r["ranks"], r["numel"], r["tensors"], r["chunks"], a["us"], a["GB/s"], a["GB/s"] / 80.0, ua["us"], ua["us"] / a["us"],
+                    l["us"], l["GB/s"], ul["us"], ul["us"] / l["us"]))
+    return 0
+
+
 def mode_epilogue(argv) -> int:
     ap = argparse.ArgumentParser(prog="bench.py --mode epilogue")
     ap.add_argument("--steps", type=int, default=400)
@@ -343,4 +387,4 @@ def mode_small(argv) -> int:
 
 
 def main(mode: str, argv) -> int:
-    return {"sweep": mode_sweep, "rsweep": mode_rsweep, "cold": mode_cold, "epilogue": mode_epilogue, "small": mode_small}[mode](argv)
+    return {"sweep": mode_sweep, "rsweep": mode_rsweep, "cold": mode_cold, "sliced": mode_sliced, "epilogue": mode_epilogue, "small": mode_small}[mode](argv)
