@@ -138,7 +138,8 @@ void free_layout(Layout &L)
     if (L.d_tensors) (void)hipFree(L.d_tensors);
     if (L.d_chunks) (void)hipFree(L.d_chunks);
     if (L.d_chunks_ordered) (void)hipFree(L.d_chunks_ordered);
-    L.d_tensors = nullptr; L.d_chunks = nullptr; L.d_chunks_ordered = nullptr;
+    if (L.d_per_chunk) (void)hipFree(L.d_per_chunk);
+    L.d_tensors = nullptr; L.d_chunks = nullptr; L.d_chunks_ordered = nullptr; L.d_per_chunk = nullptr;
 }
 
 }  // namespace
@@ -317,6 +318,7 @@ int cc_plan_create_ex(const cc_tensor *tensors, int32_t T, int32_t R, int32_t ch
             for (int r = 0; r < R; ++r) d.grad[r] = x.grad[r];
             d.wd = x.weight_decay;
             d.first_chunk = (uint32_t)first;
+            d.tensor = (uint32_t)t;
             d.num_chunks = (uint32_t)((x.numel + (uint64_t)ce - 1) / (uint64_t)ce);
             if (d.num_chunks > L.most_tensor_chunks) L.most_tensor_chunks = d.num_chunks;
             first += d.num_chunks;
@@ -333,6 +335,21 @@ int cc_plan_create_ex(const cc_tensor *tensors, int32_t T, int32_t R, int32_t ch
         cc_chunk_table_fill(numels.data(), T, ce, table.data(), L.chunks);
         PLAN_TRY(hipMalloc((void **)&L.d_chunks, sizeof(Chunk) * (size_t)(L.chunks + 1)));
         if (L.chunks > 0) PLAN_TRY(hipMemcpy(L.d_chunks, table.data(), sizeof(Chunk) * (size_t)L.chunks, hipMemcpyHostToDevice));
+        if (L.block == kSmallBlock && L.chunks > 0 && L.chunks <= kPerChunkDescriptorsMax) {
+            try {
+                L.host_per_chunk.reserve((size_t)L.chunks);
+                for (int32_t t = 0; t < T; ++t)
+                    for (uint32_t i = 0; i < L.host_tensors[(size_t)t].num_chunks; ++i) {
+                        L.host_per_chunk.push_back(L.host_tensors[(size_t)t]);
+                        L.host_per_chunk.back().chunk_index = i;
+                    }
+            } catch (const std::bad_alloc &) {
+                cc_plan_destroy(p);
+                return fail(CC_ERR_NOMEM, "cc_plan_create: out of host memory");
+            }
+            PLAN_TRY(hipMalloc((void **)&L.d_per_chunk, sizeof(DevTensor) * (size_t)L.chunks));
+            PLAN_TRY(hipMemcpy(L.d_per_chunk, L.host_per_chunk.data(), sizeof(DevTensor) * (size_t)L.chunks, hipMemcpyHostToDevice));
+        }
         if (ce == kDefaultChunkElems) {
             // The ordered schedule's table: the same entries, full chunks first (tensor order = address order inside
             // each arena), then the short last chunks, which take the unpipelined path.
@@ -418,7 +435,11 @@ int cc_plan_reserve_unfused(cc_plan *p)
     HIP_TRY(hipMalloc((void **)&buf, sizeof(float) * (size_t)(p->gsum_elems + 8)));
     for (Layout &L : p->layouts) {
         for (int32_t t = 0; t < p->T; ++t) L.host_tensors[(size_t)t].gsum = buf + p->gsum_offset[(size_t)t];
-        const hipError_t e = hipMemcpy(L.d_tensors, L.host_tensors.data(), sizeof(DevTensor) * (size_t)p->T, hipMemcpyHostToDevice);
+        hipError_t e = hipMemcpy(L.d_tensors, L.host_tensors.data(), sizeof(DevTensor) * (size_t)p->T, hipMemcpyHostToDevice);
+        if (e == hipSuccess && L.d_per_chunk) {
+            for (DevTensor &c : L.host_per_chunk) c.gsum = L.host_tensors[(size_t)c.tensor].gsum;
+            e = hipMemcpy(L.d_per_chunk, L.host_per_chunk.data(), sizeof(DevTensor) * L.host_per_chunk.size(), hipMemcpyHostToDevice);
+        }
         if (e != hipSuccess) {
             (void)hipFree(buf);
             return fail(CC_ERR_HIP, "cc_plan_reserve_unfused: %s", hipGetErrorString(e));
@@ -465,7 +486,9 @@ int cc_plan_info(const cc_plan *p, uint64_t *numel, int64_t *chunks, uint64_t *t
     if (!p) return fail(CC_ERR_NULL, "cc_plan_info: plan is NULL");
     if (numel) *numel = p->numel;
     if (chunks) *chunks = p->chunks();
-    if (table_bytes) *table_bytes = sizeof(Chunk) * (uint64_t)p->chunks() + sizeof(DevTensor) * (uint64_t)p->T;   // of the layout and schedule in use
+    if (table_bytes)      // of the layout and schedule in use
+        *table_bytes = sizeof(Chunk) * (uint64_t)p->chunks() + sizeof(DevTensor) * (uint64_t)p->T
+                       + sizeof(DevTensor) * (uint64_t)p->lay().host_per_chunk.size();
     return CC_OK;
 }
 

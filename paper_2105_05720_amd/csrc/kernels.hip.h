@@ -50,6 +50,8 @@ struct DevTensor {
     float wd;
     uint32_t first_chunk;     // position of this tensor's first chunk in the table
     uint32_t num_chunks;
+    uint32_t tensor;          // index of this tensor in the plan's list
+    uint32_t chunk_index;     // per-chunk copies of the descriptor only (see locate_at): which chunk of the tensor
     uint32_t pad_;
 };
 
@@ -186,20 +188,32 @@ struct Where {
     const DevTensor *t;
     uint32_t tensor;          // index of t in the plan's tensor list
     uint32_t slot;            // position of the chunk in tensor order (first_chunk + index): where its LAMB partials go
+    uint32_t index;           // which chunk of the tensor
     uint64_t base;            // first element of the chunk inside the tensor
     uint32_t len;             // elements in this chunk (the tensor's last chunk may be short)
 };
 
-// Table entry `entry` (uniform over the workgroup) resolved through the tensor descriptor.
+// Table entry `entry` (uniform over the workgroup) resolved through the tensor descriptor.  Plans of few chunks pass
+// chunks == nullptr and, as `tensors`, one copy of the descriptor per chunk with the chunk's index in it: the workgroup
+// then knows where its data is after one trip to memory instead of two dependent ones (entry, then descriptor): 2-4 %
+// of a launch-bound step (same machine, with / without: 4.70 / 4.90 us on 398 tensors in 571 chunks, 9.60 / 9.90 us
+// on 10 tensors in 1280 chunks).
 __device__ __forceinline__ Where locate_at(const DevTensor *__restrict__ tensors, const Chunk *__restrict__ chunks,
                                            uint32_t entry, uint32_t chunk_elems)
 {
-    const Chunk c = chunks[entry];
     Where wh;
-    wh.t = tensors + c.tensor;
-    wh.tensor = c.tensor;
-    wh.slot = wh.t->first_chunk + c.index;
-    wh.base = (uint64_t)c.index * chunk_elems;
+    if (chunks == nullptr) {
+        wh.t = tensors + entry;
+        wh.tensor = wh.t->tensor;
+        wh.index = wh.t->chunk_index;
+    } else {
+        const Chunk c = chunks[entry];
+        wh.t = tensors + c.tensor;
+        wh.tensor = c.tensor;
+        wh.index = c.index;
+    }
+    wh.slot = wh.t->first_chunk + wh.index;
+    wh.base = (uint64_t)wh.index * chunk_elems;
     const uint64_t rem = wh.t->numel - wh.base;
     wh.len = rem < chunk_elems ? (uint32_t)rem : chunk_elems;
     return wh;
@@ -1136,7 +1150,7 @@ __global__ __launch_bounds__(BLOCK) void lamb_phase2_with_norms_kernel(const Dev
     const Where wh = locate(tensors, chunks, s.chunk_elems);
     double sw, su;
     tensor_sums<BLOCK>(partials + 2 * (uint64_t)wh.t->first_chunk, wh.t->num_chunks, sw, su);
-    if (wh.base == 0 && threadIdx.x == 0) {
+    if (wh.index == 0 && threadIdx.x == 0) {
         sums[2 * (uint64_t)wh.tensor] = sw;
         sums[2 * (uint64_t)wh.tensor + 1] = su;
     }

@@ -33,7 +33,7 @@ void launch_fused_adam_r(const cc_plan *p, const StepScalars &s, int32_t *flag, 
         return;
     }
     switch (p->R) {
-#define CASE(r) case r: hipLaunchKernelGGL((fused_adam_kernel<r, MODE, BLK, GF32, 2, MEM>), grid, block, 0, st, L.d_tensors, L.d_chunks, s, p->d_flag_scratch, flag); break;
+#define CASE(r) case r: hipLaunchKernelGGL((fused_adam_kernel<r, MODE, BLK, GF32, 2, MEM>), grid, block, 0, st, L.table_tensors(), L.table_chunks(), s, p->d_flag_scratch, flag); break;
         FOR_EACH_R(CASE)
 #undef CASE
     }

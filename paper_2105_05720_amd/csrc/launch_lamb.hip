@@ -20,7 +20,7 @@ void launch_lamb_phase1_r(const cc_plan *p, const StepScalars &s, int32_t *flag,
     }
     const dim3 grid((unsigned)L.chunks), block(BLK);
     switch (p->R) {
-#define CASE(r) case r: hipLaunchKernelGGL((lamb_phase1_kernel<r, BLK, GF32, MEM>), grid, block, 0, st, L.d_tensors, L.d_chunks, s, p->d_partials, p->d_flag_scratch, flag); break;
+#define CASE(r) case r: hipLaunchKernelGGL((lamb_phase1_kernel<r, BLK, GF32, MEM>), grid, block, 0, st, L.table_tensors(), L.table_chunks(), s, p->d_partials, p->d_flag_scratch, flag); break;
         FOR_EACH_R(CASE)
 #undef CASE
     }
@@ -39,7 +39,7 @@ void launch_lamb_phase1_from_sum(const cc_plan *p, const StepScalars &s, hipStre
     const Layout &L = p->lay();
     const dim3 grid((unsigned)L.chunks);
     if (p->ordered) hipLaunchKernelGGL((lamb_phase1_from_sum_ordered_kernel<kBigBlock>), dim3(ordered_grid(p)), dim3(kBigBlock), 0, st, ORDERED_ARGS(p, kSpanFromSum), s, p->d_partials, p->d_queue);
-    else BY_BLOCK_MEM(p, p->mem_lamb, hipLaunchKernelGGL((lamb_phase1_from_sum_kernel<BLK, MEM>), grid, dim3(BLK), 0, st, L.d_tensors, L.d_chunks, s, p->d_partials));
+    else BY_BLOCK_MEM(p, p->mem_lamb, hipLaunchKernelGGL((lamb_phase1_from_sum_kernel<BLK, MEM>), grid, dim3(BLK), 0, st, L.table_tensors(), L.table_chunks(), s, p->d_partials));
 }
 
 int lamb_phase2_impl(cc_plan *p, const StepScalars &s, const int32_t *flag, hipStream_t st, bool emit16)
@@ -53,8 +53,8 @@ int lamb_phase2_impl(cc_plan *p, const StepScalars &s, const int32_t *flag, hipS
         return launched("lamb_phase2_ordered_kernel");
     }
     const dim3 grid((unsigned)L.chunks);
-    if (emit16) BY_BLOCK_MEM(p, p->mem_lamb, hipLaunchKernelGGL((lamb_phase2_kernel<true, BLK, MEM>), grid, dim3(BLK), 0, st, L.d_tensors, L.d_chunks, s, p->d_sums, flag));
-    else BY_BLOCK_MEM(p, p->mem_lamb, hipLaunchKernelGGL((lamb_phase2_kernel<false, BLK, MEM>), grid, dim3(BLK), 0, st, L.d_tensors, L.d_chunks, s, p->d_sums, flag));
+    if (emit16) BY_BLOCK_MEM(p, p->mem_lamb, hipLaunchKernelGGL((lamb_phase2_kernel<true, BLK, MEM>), grid, dim3(BLK), 0, st, L.table_tensors(), L.table_chunks(), s, p->d_sums, flag));
+    else BY_BLOCK_MEM(p, p->mem_lamb, hipLaunchKernelGGL((lamb_phase2_kernel<false, BLK, MEM>), grid, dim3(BLK), 0, st, L.table_tensors(), L.table_chunks(), s, p->d_sums, flag));
     return launched("lamb_phase2_kernel");
 }
 
@@ -62,7 +62,7 @@ int lamb_phase2_with_norms(cc_plan *p, const StepScalars &s, const int32_t *flag
 {
     const Layout &L = p->lay();
     const dim3 grid((unsigned)L.chunks);
-    BY_BLOCK_MEM(p, p->mem_lamb, hipLaunchKernelGGL((lamb_phase2_with_norms_kernel<true, BLK, MEM>), grid, dim3(BLK), 0, st, L.d_tensors, L.d_chunks, s, p->d_partials, p->d_sums, flag));
+    BY_BLOCK_MEM(p, p->mem_lamb, hipLaunchKernelGGL((lamb_phase2_with_norms_kernel<true, BLK, MEM>), grid, dim3(BLK), 0, st, L.table_tensors(), L.table_chunks(), s, p->d_partials, p->d_sums, flag));
     return launched("lamb_phase2_with_norms_kernel");
 }
 

@@ -20,7 +20,7 @@ void launch_reduce_r(const cc_plan *p, const StepScalars &s, int32_t *flag, hipS
     }
     const dim3 grid((unsigned)L.chunks), block(BLK);
     switch (p->R) {
-#define CASE(r) case r: hipLaunchKernelGGL((reduce_kernel<r, BLK, GF32, MEM>), grid, block, 0, st, L.d_tensors, L.d_chunks, s, p->d_flag_scratch, flag); break;
+#define CASE(r) case r: hipLaunchKernelGGL((reduce_kernel<r, BLK, GF32, MEM>), grid, block, 0, st, L.table_tensors(), L.table_chunks(), s, p->d_flag_scratch, flag); break;
         FOR_EACH_R(CASE)
 #undef CASE
     }
@@ -41,7 +41,7 @@ void launch_reduce_half_b(const cc_plan *p, const StepScalars &s, int32_t *flag,
     }
     const dim3 grid((unsigned)L.chunks), block(BLK);
     switch (p->R) {
-#define CASE(r) case r: hipLaunchKernelGGL((reduce_half_kernel<r, BLK, MEM>), grid, block, 0, st, L.d_tensors, L.d_chunks, s, p->d_flag_scratch, flag); break;
+#define CASE(r) case r: hipLaunchKernelGGL((reduce_half_kernel<r, BLK, MEM>), grid, block, 0, st, L.table_tensors(), L.table_chunks(), s, p->d_flag_scratch, flag); break;
         FOR_EACH_R(CASE)
 #undef CASE
     }
@@ -63,10 +63,10 @@ void launch_adam_from_sum_b(const cc_plan *p, const StepScalars &s, const int32_
     }
     const dim3 grid((unsigned)L.chunks), block(BLK);
     switch (mode) {
-        case 0: hipLaunchKernelGGL((adam_from_sum_kernel<0, BLK, SUM16, MEM>), grid, block, 0, st, L.d_tensors, L.d_chunks, s, flag); break;
-        case 1: hipLaunchKernelGGL((adam_from_sum_kernel<1, BLK, SUM16, MEM>), grid, block, 0, st, L.d_tensors, L.d_chunks, s, flag); break;
-        case 2: hipLaunchKernelGGL((adam_from_sum_kernel<2, BLK, SUM16, MEM>), grid, block, 0, st, L.d_tensors, L.d_chunks, s, flag); break;
-        default: hipLaunchKernelGGL((adam_from_sum_kernel<3, BLK, SUM16, MEM>), grid, block, 0, st, L.d_tensors, L.d_chunks, s, flag); break;
+        case 0: hipLaunchKernelGGL((adam_from_sum_kernel<0, BLK, SUM16, MEM>), grid, block, 0, st, L.table_tensors(), L.table_chunks(), s, flag); break;
+        case 1: hipLaunchKernelGGL((adam_from_sum_kernel<1, BLK, SUM16, MEM>), grid, block, 0, st, L.table_tensors(), L.table_chunks(), s, flag); break;
+        case 2: hipLaunchKernelGGL((adam_from_sum_kernel<2, BLK, SUM16, MEM>), grid, block, 0, st, L.table_tensors(), L.table_chunks(), s, flag); break;
+        default: hipLaunchKernelGGL((adam_from_sum_kernel<3, BLK, SUM16, MEM>), grid, block, 0, st, L.table_tensors(), L.table_chunks(), s, flag); break;
     }
 }
 
@@ -104,7 +104,7 @@ int cast_launch(cc_plan *p, const StepScalars &s, const int32_t *flag, hipStream
         return launched("cast_ordered_kernel");
     }
     const dim3 grid((unsigned)p->chunks());
-    BY_BLOCK(p, hipLaunchKernelGGL((cast_kernel<BLK, MEM>), grid, dim3(BLK), 0, st, p->lay().d_tensors, p->lay().d_chunks, s, flag, guarded));
+    BY_BLOCK(p, hipLaunchKernelGGL((cast_kernel<BLK, MEM>), grid, dim3(BLK), 0, st, p->lay().table_tensors(), p->lay().table_chunks(), s, flag, guarded));
     return launched("cast_kernel");
 }
 

@@ -19,6 +19,7 @@ constexpr int32_t kLargeChunkElems = 16384;      // four sweeps of a 512-thread 
 constexpr uint64_t kSmallShardElems = 64u << 20; // below this many elements the default chunk is the small one (size sweep)
 constexpr int32_t kMaxChunkElems = 1 << 24;      // lane offsets inside a chunk are 32-bit byte offsets
 constexpr int kBigBlock = 512, kSmallBlock = 128;
+constexpr int64_t kPerChunkDescriptorsMax = 2048; // chunks up to which a small-chunk layout keeps a descriptor per chunk (224 B each)
 constexpr int kOrderedMaxF32Slices = 8;           // fp32 slices: the ordered schedule wins up to 8 (config-2 list: 3.18 against 3.41 ms), at 16 two chunks spill
 constexpr int64_t kOrderedMinChunksPerCu = 8;    // below this many chunks per compute unit a plan keeps one workgroup per chunk
 // AUTO cache policy: plain loads and write-through stores instead of non-temporal accesses while the step's buffers (R
@@ -55,6 +56,11 @@ struct Layout {
     std::vector<DevTensor> host_tensors;         // host mirror of the device descriptors (first_chunk / num_chunks of this chunking)
     DevTensor *d_tensors = nullptr;
     Chunk *d_chunks = nullptr;                   // tensor order
+    std::vector<DevTensor> host_per_chunk;       // few chunks only: the descriptor once per chunk (see locate_at), else empty
+    DevTensor *d_per_chunk = nullptr;
+    // what the one-workgroup-per-chunk kernels take as their table
+    const DevTensor *table_tensors() const { return d_per_chunk ? d_per_chunk : d_tensors; }
+    const Chunk *table_chunks() const { return d_per_chunk ? nullptr : d_chunks; }
     Chunk *d_chunks_ordered = nullptr;           // the ordered schedule's order; only for kDefaultChunkElems
 };
 

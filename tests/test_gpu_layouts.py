@@ -184,3 +184,20 @@ def test_mid_size_shard_under_the_automatic_cache_policy(fn, ofn, log2n, R, poli
     run_steps(sh, ost, fn, ofn, [hyper_pair(step=t) for t in (1, 2)], "2^%d policy %d" % (log2n, policy),
               lambda i: seeded_grads(sh, 800 + i, 1e-3), expect_flags=[0, 0])
     sh.destroy()
+
+
+@pytest.mark.parametrize("fn,ofn", [(cc.cc_fused_adam_step, oracle.adam_step), (cc.cc_fused_lamb_step, oracle.lamb_step),
+                                    (cc.cc_unfused_adam_step, oracle.adam_step)])
+def test_both_forms_of_the_chunk_table(fn, ofn):
+    """Layouts of up to 2048 chunks give the kernels one copy of the tensor's descriptor per chunk, larger ones a chunk
+    entry that points at the descriptor.  A list of exactly 2048 chunks and the same list with one more one-element
+    tensor (2049 chunks) are each checked against the oracle, every element, two steps."""
+    shared = [1024 * 700 + 5, 1024 * 1300, 17, 1024 * 44 + 1000, 1]            # 701 + 1300 + 1 + 45 + 1 = 2048 chunks
+    for numels in (shared, shared + [1]):
+        sh = Shard(numels, wds_for(numels), 3, align_elems=8, chunk_elems=1024, unfused=True)
+        assert cc.cc_plan_info(sh.plans[0])[1] == len(numels) - 5 + 2048
+        seeded_state(sh, 31)
+        ost = OracleState(sh, range(len(numels)))
+        run_steps(sh, ost, fn, ofn, [hyper_pair(step=t) for t in (1, 2)], "%d chunks" % (len(numels) - 5 + 2048),
+                  lambda i: seeded_grads(sh, 310 + i, 1e-2), expect_flags=[0, 0])
+        sh.destroy()
