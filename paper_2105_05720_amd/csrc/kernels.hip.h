@@ -193,36 +193,43 @@ struct Where {
     uint32_t len;             // elements in this chunk (the tensor's last chunk may be short)
 };
 
-// Table entry `entry` (uniform over the workgroup) resolved through the tensor descriptor.  Plans of few chunks pass
-// chunks == nullptr and, as `tensors`, one copy of the descriptor per chunk with the chunk's index in it: the workgroup
-// then knows where its data is after one trip to memory instead of two dependent ones (entry, then descriptor): 2-4 %
-// of a launch-bound step (same machine, with / without: 4.70 / 4.90 us on 398 tensors in 571 chunks, 9.60 / 9.90 us
-// on 10 tensors in 1280 chunks).
-__device__ __forceinline__ Where locate_at(const DevTensor *__restrict__ tensors, const Chunk *__restrict__ chunks,
-                                           uint32_t entry, uint32_t chunk_elems)
+// What is left to derive once the descriptor and the chunk's index are known.
+__device__ __forceinline__ void finish_where(Where &wh, uint32_t chunk_elems)
 {
-    Where wh;
-    if (chunks == nullptr) {
-        wh.t = tensors + entry;
-        wh.tensor = wh.t->tensor;
-        wh.index = wh.t->chunk_index;
-    } else {
-        const Chunk c = chunks[entry];
-        wh.t = tensors + c.tensor;
-        wh.tensor = c.tensor;
-        wh.index = c.index;
-    }
     wh.slot = wh.t->first_chunk + wh.index;
     wh.base = (uint64_t)wh.index * chunk_elems;
     const uint64_t rem = wh.t->numel - wh.base;
     wh.len = rem < chunk_elems ? (uint32_t)rem : chunk_elems;
+}
+
+// Table entry `entry` (uniform over the workgroup) resolved through the tensor descriptor.
+__device__ __forceinline__ Where locate_at(const DevTensor *__restrict__ tensors, const Chunk *__restrict__ chunks,
+                                           uint32_t entry, uint32_t chunk_elems)
+{
+    const Chunk c = chunks[entry];
+    Where wh;
+    wh.t = tensors + c.tensor;
+    wh.tensor = c.tensor;
+    wh.index = c.index;
+    finish_where(wh, chunk_elems);
     return wh;
 }
 
+// The chunk of this workgroup under the one-workgroup-per-chunk launches.  Plans of few chunks pass chunks == nullptr
+// and, as `tensors`, one copy of the descriptor per chunk with the chunk's index in it: the workgroup then knows where
+// its data is after one trip to memory instead of two dependent ones (entry, then descriptor): 2-4 % of a launch-bound
+// step (same machine, with / without: 4.70 / 4.90 us on 398 tensors in 571 chunks, 9.60 / 9.90 us on 10 tensors in
+// 1280 chunks).
 __device__ __forceinline__ Where locate(const DevTensor *__restrict__ tensors, const Chunk *__restrict__ chunks,
                                         uint32_t chunk_elems)
 {
-    return locate_at(tensors, chunks, blockIdx.x, chunk_elems);
+    if (chunks != nullptr) return locate_at(tensors, chunks, blockIdx.x, chunk_elems);
+    Where wh;
+    wh.t = tensors + blockIdx.x;
+    wh.tensor = wh.t->tensor;
+    wh.index = wh.t->chunk_index;
+    finish_where(wh, chunk_elems);
+    return wh;
 }
 
 // The overflow flag is produced by the same launch that does the work, with no clearing launch in front of it and
